@@ -1,0 +1,202 @@
+/*
+ * shadow.h -- C ABI of the shadow-update library for AMD MI355X (gfx950).
+ *
+ * The library keeps a checkpoint replica of a model (fp32 parameters plus the
+ * AdamW moments m and v) in HBM and, once per training iteration, folds the
+ * gradient buckets of the W data-parallel workers into one reduced gradient
+ * and applies the trainers' optimizer step to the replica.  This is the work
+ * of a shadow node in Checkmate (arxiv 2507.13522): section 4 overview, steps
+ * 3 and 4; section 4.2.2 (bucket -> parameter mapping); section 4.2.3
+ * (updating the checkpoint); section 4.2.4 (functional optimizers: every
+ * element is updated independently, so buckets may be applied one by one).
+ *
+ * Conventions
+ *   - Every function returns 0 (SHADOW_OK) or a negative shadow_status; no
+ *     function aborts or throws.  On an error the replica is left untouched
+ *     unless the status is SHADOW_EHIP (a runtime failure after work was
+ *     enqueued; the context must then be destroyed).
+ *   - "device pointer" = HBM address valid on the current HIP device;
+ *     "host pointer"   = ordinary process memory.  Every array argument says
+ *     which one it is.
+ *   - The library never frees or reallocates caller memory; arenas and
+ *     gradient views are BORROWED.  It allocates only small device tables
+ *     (weight-decay map, norm partials) that it owns.
+ *   - Calls on one context are not thread-safe; use one host thread per context.
+ */
+#ifndef SHADOW_H
+#define SHADOW_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SHADOW_OK      = 0,
+    SHADOW_EINVAL  = -1,  /* null / misaligned pointer, bad hyper-parameter, bad size          */
+    SHADOW_EBUCKET = -2,  /* bucket id out of range                                            */
+    SHADOW_EDUP    = -3,  /* bucket already applied in this iteration (section 4.1: a gradient
+                             must reach the shadow exactly once per iteration)                 */
+    SHADOW_ESTEP   = -4,  /* step is not last completed step + 1 (a lost or replayed iteration) */
+    SHADOW_EBUSY   = -5,  /* operation needs an iteration boundary but an iteration is open    */
+    SHADOW_EHIP    = -6,  /* HIP runtime failure; shadow_last_hip_error() has the text         */
+    SHADOW_ENOMEM  = -7   /* host or device allocation failed                                  */
+} shadow_status;
+
+enum { SHADOW_GRAD_F32 = 0, SHADOW_GRAD_BF16 = 1 };
+enum { SHADOW_REDUCE_MEAN = 0, SHADOW_REDUCE_SUM = 1 };
+enum { SHADOW_MAX_WORKERS = 64, SHADOW_MAX_STREAMS = 16 };
+
+/* One model tensor.  Tensors are listed in MODEL order (first layer first). */
+typedef struct {
+    uint64_t numel;         /* >= 1, no alignment requirement                          */
+    uint32_t weight_decay;  /* 1: decoupled weight decay applies; 0: masked (bias/norm) */
+    uint32_t reserved;      /* must be 0                                               */
+} shadow_tensor_desc;
+
+/* Optimizer and reduce settings (AdamW: section 6; reduce: section 2.1). */
+typedef struct {
+    float    lr;             /* >= 0                                                       */
+    float    beta1;          /* in [0, 1)                                                  */
+    float    beta2;          /* in [0, 1)                                                  */
+    float    eps;            /* > 0                                                        */
+    float    weight_decay;   /* >= 0; p *= (1 - lr*weight_decay) on tensors with the flag  */
+    float    max_grad_norm;  /* > 0: clip the reduced gradient's global L2 norm; <= 0: off */
+    uint32_t num_workers;    /* W in [1, SHADOW_MAX_WORKERS]                               */
+    uint32_t grad_dtype;     /* SHADOW_GRAD_F32 or SHADOW_GRAD_BF16                        */
+    uint32_t reduce_op;      /* SHADOW_REDUCE_MEAN (sum * float(1/W)) or SHADOW_REDUCE_SUM */
+    uint32_t num_streams;    /* HIP streams buckets are spread over, [1, SHADOW_MAX_STREAMS] */
+} shadow_hparams;
+
+/* ------------------------------------------------------------------------ *
+ * Parameter layout (host only; needs no GPU).  Section 4.2.2.
+ *
+ * Tensors are bin-packed into buckets walking from the LAST tensor to the
+ * first: a tensor joins the open bucket while the bucket's gradient bytes stay
+ * <= bucket_cap_bytes, otherwise a new bucket is opened; a tensor larger than
+ * the cap closes the open bucket and gets a bucket of its own.  Bucket 0 is
+ * the first one formed (last layers).  Inside a bucket tensors lie back to
+ * back in the order they were added, exactly as in the gradient views.
+ *
+ * The arena (param, m, v and the reduced-gradient scratch share this layout)
+ * is bucket-major; every bucket starts on a 256-byte boundary (64 floats), so
+ * arena_numel >= num_params; the gaps are owned and kept at zero by the library.
+ * ------------------------------------------------------------------------ */
+typedef struct shadow_layout shadow_layout;
+
+/* tensors: host pointer, num_tensors entries.  bucket_of_tensor: host pointer
+ * or NULL; if given it fixes the bucket id of every tensor (ids must be dense,
+ * 0..B-1) and bucket_cap_bytes is ignored; members of a bucket are still laid
+ * out last-tensor-first.  grad_elem_bytes: 2 or 4.  *out is owned by the
+ * caller until shadow_layout_destroy. */
+int32_t shadow_layout_create(shadow_layout** out, const shadow_tensor_desc* tensors, uint32_t num_tensors,
+                             const uint32_t* bucket_of_tensor, uint32_t grad_elem_bytes,
+                             uint64_t bucket_cap_bytes);
+int32_t shadow_layout_destroy(shadow_layout* layout);
+int32_t shadow_layout_num_buckets(const shadow_layout* layout, uint32_t* out);
+int32_t shadow_layout_num_params(const shadow_layout* layout, uint64_t* out);
+/* floats the caller must allocate for each of param, m, v (and scratch) */
+int32_t shadow_layout_arena_numel(const shadow_layout* layout, uint64_t* out);
+/* bucket -> its start in the arena (in floats), its element count, its tensor count */
+int32_t shadow_layout_bucket(const shadow_layout* layout, uint32_t bucket, uint64_t* arena_offset,
+                             uint64_t* numel, uint32_t* num_tensors);
+/* tensor (model-order index) -> bucket, offset inside the bucket, offset in the arena (elements) */
+int32_t shadow_layout_tensor(const shadow_layout* layout, uint32_t tensor, uint32_t* bucket,
+                             uint64_t* offset_in_bucket, uint64_t* arena_offset);
+
+/* ------------------------------------------------------------------------ *
+ * The replica.
+ * ------------------------------------------------------------------------ */
+typedef struct shadow_ctx shadow_ctx;
+
+/* Create a replica over caller-allocated arenas on the current HIP device.
+ *   layout     host object, copied (may be destroyed afterwards).
+ *   hp         host pointer.
+ *   d_param, d_m, d_v   device pointers, arena_numel floats each, 256-byte
+ *              aligned, borrowed until shadow_destroy.  The caller has already
+ *              written the initial state at the layout's offsets (fresh start:
+ *              parameters, m = v = 0; restore: a snapshot's contents).  The
+ *              library zeroes the alignment gaps.
+ *   d_reduced  device pointer, arena_numel floats, 256-byte aligned, borrowed:
+ *              holds the reduced gradient between the fold and the update when
+ *              clipping is on (the norm over ALL buckets must be known before
+ *              any element is updated).  Must be NULL when clipping is off.
+ *   start_step iterations already applied to this state (0 for a fresh
+ *              replica; a snapshot's step when restoring).  The first
+ *              iteration applied is start_step + 1; Adam's bias correction
+ *              uses that 1-based count.
+ *   streams    host array of hp->num_streams hipStream_t handles (for example
+ *              torch streams' .cuda_stream), borrowed; or NULL: the library
+ *              creates and owns default-priority streams.
+ */
+int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_hparams* hp,
+                    float* d_param, float* d_m, float* d_v, float* d_reduced,
+                    uint64_t start_step, void* const* streams);
+
+/* Apply one bucket of iteration `step`: fold the W gradient views and (when
+ * clipping is off) update the bucket's parameters in the same kernel; when
+ * clipping is on the fold stores the reduced gradient and its sum of squares,
+ * and the call that delivers the last missing bucket of the iteration also
+ * enqueues the norm and the update of every bucket.
+ *   d_grad_views  HOST array of W DEVICE pointers; view w holds worker w's
+ *                 gradient for this bucket: numel(bucket) elements of
+ *                 grad_dtype, contiguous, in the bucket's element order,
+ *                 16-byte aligned.  The data must be ready when the call is
+ *                 made (or be ordered before it on shadow_bucket_stream) and
+ *                 stay unchanged until the enqueued work has run
+ *                 (shadow_sync, or stream order on that stream).
+ *   step          must equal last completed step + 1; buckets of one
+ *                 iteration may come in any order, each exactly once.
+ * Asynchronous: returns after enqueueing.  Errors: EINVAL, EBUCKET, EDUP,
+ * ESTEP, EHIP. */
+int32_t shadow_apply_bucket(shadow_ctx* ctx, uint32_t bucket_id, const void* const* d_grad_views,
+                            uint64_t step);
+
+/* Copy the replica at the last completed iteration: dst_* are device pointers
+ * or pinned host pointers of arena_numel floats each (NULL = skip that array).
+ * The copies are enqueued after the iteration's last kernel and before any
+ * later iteration's work; they have finished when shadow_sync returns.
+ * *out_step (host pointer, may be NULL) receives the iteration count.
+ * SHADOW_EBUSY if an iteration is partly applied: a checkpoint is only
+ * consistent at iteration granularity (section 4, "remain up to date"). */
+int32_t shadow_snapshot(shadow_ctx* ctx, float* dst_param, float* dst_m, float* dst_v, uint64_t* out_step);
+
+/* Block the host until everything enqueued by this context has run. */
+int32_t shadow_sync(shadow_ctx* ctx);
+int32_t shadow_destroy(shadow_ctx* ctx);
+
+/* Queries (host pointers out). */
+int32_t shadow_step(const shadow_ctx* ctx, uint64_t* completed_step, uint32_t* buckets_pending);
+/* stream (hipStream_t) that work for this bucket is enqueued on */
+int32_t shadow_bucket_stream(const shadow_ctx* ctx, uint32_t bucket_id, void** out_stream);
+/* Clip coefficient c = min(1, max_norm/(||r||_2 + 1e-6)) and sum of squares of
+ * the last completed iteration; synchronizes.  EINVAL if clipping is off. */
+int32_t shadow_clip_state(shadow_ctx* ctx, float* out_coef, double* out_sumsq);
+/* Learning rate for iterations that start after this call (cosine or any
+ * other schedule is evaluated by the caller; section 6).  EBUSY mid-iteration. */
+int32_t shadow_set_lr(shadow_ctx* ctx, float lr);
+
+/* Per-kernel timing with HIP events on the streams the kernels run on.
+ * kind: 0 fused fold+AdamW, 1 fold+sum-of-squares, 2 norm finalize, 3 AdamW sweep. */
+enum { SHADOW_K_FOLD_ADAMW = 0, SHADOW_K_FOLD_SUMSQ = 1, SHADOW_K_NORM = 2, SHADOW_K_ADAMW = 3, SHADOW_K_COUNT = 4 };
+int32_t shadow_profile_enable(shadow_ctx* ctx, int32_t on);
+/* Synchronizes, returns and resets the launches and summed duration of one kind. */
+int32_t shadow_profile_read(shadow_ctx* ctx, uint32_t kind, uint64_t* launches, double* total_ms);
+
+/* Plain device-to-device copy kernel of `bytes` (multiple of 16) on `stream`
+ * (NULL = default): a known-traffic yardstick for bandwidth counters. */
+int32_t shadow_copy_probe(void* d_dst, const void* d_src, uint64_t bytes, void* stream);
+
+const char* shadow_strerror(int32_t status);
+const char* shadow_last_hip_error(void);
+/* Tuning knobs of the launch shapes (for measurement sweeps): "fold_grid_cap"
+ * (most blocks of a per-bucket kernel) and "adamw_grid_cap" (most blocks of the
+ * whole-arena sweep); larger inputs are covered by grid-stride loops.  Applies
+ * to contexts created later. */
+int32_t shadow_set_tunable(const char* name, int64_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHADOW_H */

@@ -222,15 +222,17 @@ class OracleShadow:
     def __init__(self, layout: Layout, hp: HParams, params: Sequence[np.ndarray],
                  precision: str = "f32", start_step: int = 0,
                  m: Optional[Sequence[np.ndarray]] = None, v: Optional[Sequence[np.ndarray]] = None):
+        """params (and m, v if given): one array per bucket; an entry may be None for a
+        bucket whose state is not kept (then only update_bucket on the others is usable)."""
         self.layout, self.hp, self.precision = layout, hp, precision
         self.dt = np.float32 if precision == "f32" else np.float64
-        self.p = [np.array(x, dtype=self.dt).copy() for x in params]
-        self.m = [np.zeros(b.numel, self.dt) for b in layout.buckets] if m is None else \
-                 [np.array(x, dtype=self.dt).copy() for x in m]
-        self.v = [np.zeros(b.numel, self.dt) for b in layout.buckets] if v is None else \
-                 [np.array(x, dtype=self.dt).copy() for x in v]
+        self.p = [None if x is None else np.array(x, dtype=self.dt).copy() for x in params]
+        zeros = [None if x is None else np.zeros(x.size, self.dt) for x in self.p]
+        self.m = zeros if m is None else [None if x is None else np.array(x, dtype=self.dt).copy() for x in m]
+        self.v = [None if x is None else z.copy() for x, z in zip(self.p, zeros)] if v is None else \
+                 [None if x is None else np.array(x, dtype=self.dt).copy() for x in v]
         for b, arr in zip(layout.buckets, self.p):
-            assert arr.size == b.numel
+            assert arr is None or arr.size == b.numel
         self.t = int(start_step)
         self.last_coef = None
         self.last_sumsq = None

@@ -1,0 +1,231 @@
+"""ctypes binding of include/shadow.h: argument marshalling only.
+
+Function names follow the C ABI (``shadow_layout_create`` -> ``Layout``,
+``shadow_init`` -> ``Shadow`` and its methods ``apply_bucket``, ``snapshot``,
+``sync`` ...).  Pointers are plain integers (for torch tensors: ``data_ptr()``),
+streams are ``hipStream_t`` handles as integers (``torch.cuda.Stream.cuda_stream``).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+from . import build as _build
+
+GRAD_F32, GRAD_BF16 = 0, 1
+REDUCE_MEAN, REDUCE_SUM = 0, 1
+K_FOLD_ADAMW, K_FOLD_SUMSQ, K_NORM, K_ADAMW = 0, 1, 2, 3
+
+OK, EINVAL, EBUCKET, EDUP, ESTEP, EBUSY, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [("numel", C.c_uint64), ("weight_decay", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class HParams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("max_grad_norm", C.c_float), ("num_workers", C.c_uint32),
+                ("grad_dtype", C.c_uint32), ("reduce_op", C.c_uint32), ("num_streams", C.c_uint32)]
+
+
+class ShadowError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = shadow_strerror(status)
+        if status == EHIP:
+            msg += ": " + lib().shadow_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+_lib = None
+
+_SIGS = {
+    "shadow_layout_create": [C.POINTER(C.c_void_p), C.POINTER(TensorDesc), C.c_uint32, C.POINTER(C.c_uint32), C.c_uint32, C.c_uint64],
+    "shadow_layout_destroy": [C.c_void_p],
+    "shadow_layout_num_buckets": [C.c_void_p, C.POINTER(C.c_uint32)],
+    "shadow_layout_num_params": [C.c_void_p, C.POINTER(C.c_uint64)],
+    "shadow_layout_arena_numel": [C.c_void_p, C.POINTER(C.c_uint64)],
+    "shadow_layout_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)],
+    "shadow_layout_tensor": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)],
+    "shadow_init": [C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(HParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p)],
+    "shadow_apply_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64],
+    "shadow_snapshot": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64)],
+    "shadow_sync": [C.c_void_p],
+    "shadow_destroy": [C.c_void_p],
+    "shadow_step": [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)],
+    "shadow_bucket_stream": [C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)],
+    "shadow_clip_state": [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_double)],
+    "shadow_set_lr": [C.c_void_p, C.c_float],
+    "shadow_profile_enable": [C.c_void_p, C.c_int32],
+    "shadow_profile_read": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_double)],
+    "shadow_copy_probe": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p],
+    "shadow_set_tunable": [C.c_char_p, C.c_int64],
+}
+EXPORTS = sorted(list(_SIGS) + ["shadow_strerror", "shadow_last_hip_error"])
+
+
+def lib() -> C.CDLL:
+    """Load libshadow.so (building it with hipcc only if no built library exists)."""
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build_library()
+        L = C.CDLL(path)
+        for name, args in _SIGS.items():
+            fn = getattr(L, name)
+            fn.argtypes = args
+            fn.restype = C.c_int32
+        L.shadow_strerror.argtypes = [C.c_int32]
+        L.shadow_strerror.restype = C.c_char_p
+        L.shadow_last_hip_error.argtypes = []
+        L.shadow_last_hip_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def shadow_strerror(status: int) -> str:
+    return lib().shadow_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise ShadowError(status, where)
+
+
+def shadow_set_tunable(name: str, value: int) -> None:
+    _check(lib().shadow_set_tunable(name.encode(), int(value)), "shadow_set_tunable")
+
+
+def shadow_copy_probe(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
+    _check(lib().shadow_copy_probe(dst, src, nbytes, stream), "shadow_copy_probe")
+
+
+class Layout:
+    """shadow_layout_*: tensors = [(numel, weight_decay_flag)] in model order."""
+
+    def __init__(self, tensors: Sequence[Tuple[int, bool]], grad_elem_bytes: int, bucket_cap_bytes: int = 0,
+                 bucket_of_tensor: Optional[Sequence[int]] = None):
+        n = len(tensors)
+        arr = (TensorDesc * max(n, 1))()
+        for i, (numel, wd) in enumerate(tensors):
+            arr[i].numel, arr[i].weight_decay, arr[i].reserved = int(numel), int(bool(wd)), 0
+        fixed = None
+        if bucket_of_tensor is not None:
+            if len(bucket_of_tensor) != n:
+                raise ValueError("bucket_of_tensor length")
+            fixed = (C.c_uint32 * max(n, 1))(*[int(b) for b in bucket_of_tensor])
+        h = C.c_void_p()
+        _check(lib().shadow_layout_create(C.byref(h), arr, n, fixed, grad_elem_bytes, bucket_cap_bytes), "shadow_layout_create")
+        self._h = h
+        self.num_tensors = n
+        v32, v64 = C.c_uint32(), C.c_uint64()
+        _check(lib().shadow_layout_num_buckets(h, C.byref(v32)), "shadow_layout_num_buckets")
+        self.num_buckets = v32.value
+        _check(lib().shadow_layout_num_params(h, C.byref(v64)), "shadow_layout_num_params")
+        self.num_params = v64.value
+        _check(lib().shadow_layout_arena_numel(h, C.byref(v64)), "shadow_layout_arena_numel")
+        self.arena_numel = v64.value
+
+    def bucket(self, b: int) -> Tuple[int, int, int]:
+        """-> (arena offset, numel, number of tensors)"""
+        off, n, nt = C.c_uint64(), C.c_uint64(), C.c_uint32()
+        _check(lib().shadow_layout_bucket(self._h, b, C.byref(off), C.byref(n), C.byref(nt)), "shadow_layout_bucket")
+        return off.value, n.value, nt.value
+
+    def tensor(self, t: int) -> Tuple[int, int, int]:
+        """-> (bucket, offset in bucket, arena offset)"""
+        b, ob, oa = C.c_uint32(), C.c_uint64(), C.c_uint64()
+        _check(lib().shadow_layout_tensor(self._h, t, C.byref(b), C.byref(ob), C.byref(oa)), "shadow_layout_tensor")
+        return b.value, ob.value, oa.value
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            lib().shadow_layout_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Shadow:
+    """shadow_init .. shadow_destroy.  Arena arguments are device addresses (ints)."""
+
+    def __init__(self, layout: Layout, hp: HParams, d_param: int, d_m: int, d_v: int, d_reduced: Optional[int] = None,
+                 start_step: int = 0, streams: Optional[Sequence[int]] = None):
+        self.layout = layout
+        self.hp = hp
+        sarr = None
+        if streams is not None:
+            if len(streams) != hp.num_streams:
+                raise ValueError("need hp.num_streams stream handles")
+            sarr = (C.c_void_p * len(streams))(*[int(s) for s in streams])
+        h = C.c_void_p()
+        _check(lib().shadow_init(C.byref(h), layout._h, C.byref(hp), d_param, d_m, d_v, d_reduced or None,
+                                 start_step, sarr), "shadow_init")
+        self._h = h
+        self._views = {}
+
+    def views_array(self, ptrs: Sequence[int]):
+        """Marshal W device addresses once; the result can be passed to apply_bucket repeatedly."""
+        return (C.c_void_p * len(ptrs))(*[int(p) for p in ptrs])
+
+    def apply_bucket(self, bucket_id: int, views, step: int) -> None:
+        if not isinstance(views, C.Array):
+            views = self.views_array(views)
+        _check(lib().shadow_apply_bucket(self._h, bucket_id, views, step), "shadow_apply_bucket")
+
+    def try_apply_bucket(self, bucket_id: int, views, step: int) -> int:
+        if not isinstance(views, C.Array):
+            views = self.views_array(views)
+        return int(lib().shadow_apply_bucket(self._h, bucket_id, views, step))
+
+    def snapshot(self, dst_param: Optional[int], dst_m: Optional[int], dst_v: Optional[int]) -> int:
+        st = C.c_uint64()
+        _check(lib().shadow_snapshot(self._h, dst_param or None, dst_m or None, dst_v or None, C.byref(st)), "shadow_snapshot")
+        return st.value
+
+    def sync(self) -> None:
+        _check(lib().shadow_sync(self._h), "shadow_sync")
+
+    def step(self) -> Tuple[int, int]:
+        s, pend = C.c_uint64(), C.c_uint32()
+        _check(lib().shadow_step(self._h, C.byref(s), C.byref(pend)), "shadow_step")
+        return s.value, pend.value
+
+    def bucket_stream(self, bucket_id: int) -> int:
+        s = C.c_void_p()
+        _check(lib().shadow_bucket_stream(self._h, bucket_id, C.byref(s)), "shadow_bucket_stream")
+        return s.value or 0
+
+    def clip_state(self) -> Tuple[float, float]:
+        c, s = C.c_float(), C.c_double()
+        _check(lib().shadow_clip_state(self._h, C.byref(c), C.byref(s)), "shadow_clip_state")
+        return c.value, s.value
+
+    def set_lr(self, lr: float) -> None:
+        _check(lib().shadow_set_lr(self._h, lr), "shadow_set_lr")
+
+    def profile_enable(self, on: bool) -> None:
+        _check(lib().shadow_profile_enable(self._h, int(on)), "shadow_profile_enable")
+
+    def profile_read(self, kind: int) -> Tuple[int, float]:
+        n, ms = C.c_uint64(), C.c_double()
+        _check(lib().shadow_profile_read(self._h, kind, C.byref(n), C.byref(ms)), "shadow_profile_read")
+        return n.value, ms.value
+
+    def destroy(self) -> None:
+        if getattr(self, "_h", None):
+            lib().shadow_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,702 @@
+// Host side of the shadow-update library: layout (section 4.2.2), exactly-once
+// bookkeeping per iteration (section 4.1), scheduling of bucket kernels on HIP
+// streams, snapshot at iteration boundaries (section 4, per-iteration
+// granularity of the checkpoint).  The C ABI is declared in include/shadow.h.
+#include "shadow_kernels.hip.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/shadow.h"
+
+using namespace shadow;
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+struct Tunables {
+    int64_t fold_grid_cap = 8192;     // blocks per bucket kernel (grid-stride beyond)
+    int64_t adamw_grid_cap = 16384;   // blocks of the whole-arena AdamW sweep
+} g_tune;
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) {                                                               \
+            g_hip_error = std::string(#expr) + ": " + hipGetErrorString(e_);                  \
+            return SHADOW_EHIP;                                                               \
+        }                                                                                     \
+    } while (0)
+
+constexpr uint64_t kAlignElems = 64;   // 256 bytes of float
+
+struct Seg {
+    uint32_t tensor;
+    uint64_t offset;   // inside the bucket
+    uint64_t numel;
+    uint8_t wd;
+};
+
+struct BucketL {
+    uint64_t arena_off = 0;
+    uint64_t numel = 0;
+    std::vector<Seg> segs;
+};
+
+}  // namespace
+
+struct shadow_layout {
+    std::vector<shadow_tensor_desc> tensors;
+    std::vector<uint32_t> bucket_of;
+    std::vector<uint64_t> off_in_bucket;
+    std::vector<BucketL> buckets;
+    uint64_t num_params = 0;
+    uint64_t arena_numel = 0;
+    uint32_t grad_elem_bytes = 0;
+};
+
+struct shadow_ctx {
+    shadow_layout lay;
+    shadow_hparams hp;
+    float *p = nullptr, *m = nullptr, *v = nullptr, *r = nullptr;
+    bool clip = false;
+    std::vector<hipStream_t> streams;
+    bool own_streams = false;
+    // device tables owned by the library
+    uint8_t* d_tile_mode = nullptr;
+    uint64_t* d_run_start = nullptr;
+    uint8_t* d_run_flag = nullptr;
+    uint32_t num_runs = 0;
+    double* d_partial = nullptr;
+    float* d_coef = nullptr;
+    double* d_sumsq = nullptr;
+    std::vector<uint32_t> slot_base, slot_count;
+    uint32_t nslots = 0;
+    // iteration state
+    uint64_t completed = 0;
+    std::vector<uint8_t> arrived;
+    uint32_t arrived_count = 0;
+    StepScalars sc{};
+    uint64_t sc_step = 0;
+    std::vector<hipEvent_t> join_ev;      // one per stream
+    hipEvent_t boundary_ev = nullptr;     // after the last kernel / copy at an iteration boundary
+    bool boundary_pending = false;        // streams must wait on boundary_ev before new work
+    std::vector<uint8_t> stream_dirty;    // stream has work since the last join
+    bool poisoned = false;
+    // profiling
+    bool profile = false;
+    struct Span { hipEvent_t a, b; };
+    std::vector<Span> spans[SHADOW_K_COUNT];
+    std::vector<hipEvent_t> ev_pool;
+};
+
+namespace {
+
+bool plan(shadow_layout& L, const uint32_t* fixed, uint64_t cap)
+{
+    const uint32_t T = uint32_t(L.tensors.size());
+    L.bucket_of.assign(T, 0);
+    uint32_t nb = 0;
+    if (fixed) {
+        uint32_t mx = 0;
+        for (uint32_t t = 0; t < T; ++t) { L.bucket_of[t] = fixed[t]; if (fixed[t] > mx) mx = fixed[t]; }
+        nb = T ? mx + 1 : 0;
+        if (nb > T) return false;
+        std::vector<uint8_t> used(nb, 0);
+        for (uint32_t t = 0; t < T; ++t) used[fixed[t]] = 1;
+        for (uint32_t b = 0; b < nb; ++b) if (!used[b]) return false;
+    } else {
+        bool open = false;
+        uint32_t cur = 0;
+        uint64_t cur_bytes = 0;
+        for (uint32_t i = T; i-- > 0;) {
+            const uint64_t size = L.tensors[i].numel * L.grad_elem_bytes;
+            if (size > cap) {                 // too big for any shared bucket: alone, and it closes the open one
+                L.bucket_of[i] = nb++;
+                open = false;
+                continue;
+            }
+            if (!open || cur_bytes + size > cap) {
+                cur = nb++;
+                cur_bytes = 0;
+                open = true;
+            }
+            L.bucket_of[i] = cur;
+            cur_bytes += size;
+        }
+    }
+    L.buckets.assign(nb, BucketL{});
+    L.off_in_bucket.assign(T, 0);
+    for (uint32_t i = T; i-- > 0;) {          // members lie in the order they were added: last tensor first
+        BucketL& b = L.buckets[L.bucket_of[i]];
+        L.off_in_bucket[i] = b.numel;
+        b.segs.push_back(Seg{i, b.numel, L.tensors[i].numel, uint8_t(L.tensors[i].weight_decay ? 1 : 0)});
+        b.numel += L.tensors[i].numel;
+    }
+    uint64_t off = 0, total = 0;
+    for (BucketL& b : L.buckets) {
+        b.arena_off = off;
+        total += b.numel;
+        off += (b.numel + kAlignElems - 1) / kAlignElems * kAlignElems;
+    }
+    L.num_params = total;
+    L.arena_numel = off;
+    return true;
+}
+
+void compute_scalars(const shadow_hparams& hp, uint64_t t, StepScalars& s)
+{
+    const double b1 = hp.beta1, b2 = hp.beta2, lr = hp.lr, wd = hp.weight_decay;
+    const double bc1 = 1.0 - std::pow(b1, double(t));
+    const double bc2 = 1.0 - std::pow(b2, double(t));
+    s.beta1 = hp.beta1;
+    s.beta2 = hp.beta2;
+    s.omb1 = float(1.0 - b1);
+    s.omb2 = float(1.0 - b2);
+    s.decay = float(1.0 - lr * wd);
+    s.step_size = float(lr / bc1);
+    s.isq = float(1.0 / std::sqrt(bc2));
+    s.eps = hp.eps;
+    s.inv_w = float(1.0 / double(hp.num_workers));
+    s.mean = hp.reduce_op == SHADOW_REDUCE_MEAN ? 1u : 0u;
+}
+
+uint32_t grid_for(uint64_t nvec, int64_t cap)
+{
+    uint64_t blocks = (nvec + kBlock - 1) / kBlock;
+    if (blocks < 1) blocks = 1;
+    if (int64_t(blocks) > cap) blocks = uint64_t(cap);
+    return uint32_t(blocks);
+}
+
+int32_t get_event(shadow_ctx* c, hipEvent_t* out)
+{
+    if (!c->ev_pool.empty()) { *out = c->ev_pool.back(); c->ev_pool.pop_back(); return SHADOW_OK; }
+    HIP_TRY(hipEventCreate(out));
+    return SHADOW_OK;
+}
+
+struct ProfScope {
+    shadow_ctx* c; uint32_t kind; hipStream_t st; hipEvent_t a = nullptr, b = nullptr; int32_t rc = SHADOW_OK;
+    ProfScope(shadow_ctx* c_, uint32_t k, hipStream_t s) : c(c_), kind(k), st(s)
+    {
+        if (!c->profile) return;
+        rc = get_event(c, &a);
+        if (rc == SHADOW_OK) rc = get_event(c, &b);
+        if (rc == SHADOW_OK && hipEventRecord(a, st) != hipSuccess) rc = SHADOW_EHIP;
+    }
+    int32_t end()
+    {
+        if (!c->profile || rc != SHADOW_OK) return rc;
+        if (hipEventRecord(b, st) != hipSuccess) return SHADOW_EHIP;
+        c->spans[kind].push_back({a, b});
+        return SHADOW_OK;
+    }
+};
+
+template <bool BF16, int W>
+void launch_fold_adamw(shadow_ctx* c, const GradViews& gv, const BucketL& b, hipStream_t st, const WdMap& map)
+{
+    const uint32_t grid = grid_for(b.numel >> 3, g_tune.fold_grid_cap);
+    k_fold_adamw<BF16, W><<<grid, kBlock, 0, st>>>(gv, c->hp.num_workers, c->p + b.arena_off, c->m + b.arena_off,
+                                                   c->v + b.arena_off, b.numel, b.arena_off, map, c->sc);
+}
+
+template <bool BF16, int W>
+void launch_fold_sumsq(shadow_ctx* c, const GradViews& gv, const BucketL& b, uint32_t bucket, hipStream_t st)
+{
+    k_fold_sumsq<BF16, W><<<c->slot_count[bucket], kBlock, 0, st>>>(gv, c->hp.num_workers, c->r + b.arena_off, b.numel,
+                                                                    c->d_partial + c->slot_base[bucket], c->sc);
+}
+
+template <bool BF16>
+void dispatch_fold(shadow_ctx* c, const GradViews& gv, const BucketL& b, uint32_t bucket, hipStream_t st, const WdMap& map)
+{
+#define SHADOW_CASE(WV)                                                                       \
+    case WV:                                                                                  \
+        if (c->clip) launch_fold_sumsq<BF16, WV>(c, gv, b, bucket, st);                       \
+        else launch_fold_adamw<BF16, WV>(c, gv, b, st, map);                                  \
+        break;
+    switch (c->hp.num_workers) {
+        SHADOW_CASE(1)
+        SHADOW_CASE(2)
+        SHADOW_CASE(4)
+        SHADOW_CASE(8)
+        SHADOW_CASE(16)
+        SHADOW_CASE(32)
+        default:
+            if (c->clip) launch_fold_sumsq<BF16, 0>(c, gv, b, bucket, st);
+            else launch_fold_adamw<BF16, 0>(c, gv, b, st, map);
+    }
+#undef SHADOW_CASE
+}
+
+WdMap wd_map(const shadow_ctx* c) { return WdMap{c->d_tile_mode, c->d_run_start, c->d_run_flag, c->num_runs}; }
+
+// stream 0 waits for everything enqueued on the other streams
+int32_t join_to_stream0(shadow_ctx* c)
+{
+    for (size_t s = 1; s < c->streams.size(); ++s) {
+        if (!c->stream_dirty[s]) continue;
+        HIP_TRY(hipEventRecord(c->join_ev[s], c->streams[s]));
+        HIP_TRY(hipStreamWaitEvent(c->streams[0], c->join_ev[s], 0));
+        c->stream_dirty[s] = 0;
+    }
+    return SHADOW_OK;
+}
+
+int32_t mark_boundary(shadow_ctx* c)
+{
+    HIP_TRY(hipEventRecord(c->boundary_ev, c->streams[0]));
+    c->boundary_pending = true;
+    return SHADOW_OK;
+}
+
+void free_ctx(shadow_ctx* c)
+{
+    if (!c) return;
+    for (auto& vec : c->spans) for (auto& sp : vec) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->join_ev) if (e) (void)hipEventDestroy(e);
+    if (c->boundary_ev) (void)hipEventDestroy(c->boundary_ev);
+    if (c->own_streams) for (hipStream_t s : c->streams) if (s) (void)hipStreamDestroy(s);
+    (void)hipFree(c->d_tile_mode);
+    (void)hipFree(c->d_run_start);
+    (void)hipFree(c->d_run_flag);
+    (void)hipFree(c->d_partial);
+    (void)hipFree(c->d_coef);
+    (void)hipFree(c->d_sumsq);
+    delete c;
+}
+
+int32_t build_tables(shadow_ctx* c)
+{
+    const shadow_layout& L = c->lay;
+    // runs of equal weight-decay flag over the arena, alignment gaps count as "no decay"
+    std::vector<uint64_t> start;
+    std::vector<uint8_t> flag;
+    auto push = [&](uint64_t s, uint8_t f) {
+        if (!flag.empty() && flag.back() == f) return;
+        start.push_back(s);
+        flag.push_back(f);
+    };
+    for (const BucketL& b : L.buckets) {
+        for (const Seg& sg : b.segs) push(b.arena_off + sg.offset, sg.wd);
+        const uint64_t end = b.arena_off + b.numel;
+        const uint64_t padded = (end + kAlignElems - 1) / kAlignElems * kAlignElems;
+        if (padded != end) push(end, 0);
+    }
+    if (start.empty()) { start.push_back(0); flag.push_back(0); }
+    c->num_runs = uint32_t(start.size());
+    const uint64_t ntiles = (L.arena_numel + (1ull << kWdTileShift) - 1) >> kWdTileShift;
+    std::vector<uint8_t> mode(ntiles ? ntiles : 1, 0);
+    for (size_t k = 0; k < start.size(); ++k) {
+        const uint64_t s = start[k], e = (k + 1 < start.size()) ? start[k + 1] : L.arena_numel;
+        if (e <= s) continue;
+        for (uint64_t t = s >> kWdTileShift; t <= ((e - 1) >> kWdTileShift); ++t) mode[t] = flag[k];
+    }
+    for (size_t k = 1; k < start.size(); ++k)
+        if (start[k] & ((1ull << kWdTileShift) - 1)) mode[start[k] >> kWdTileShift] = 2;
+    HIP_TRY(hipMalloc(&c->d_tile_mode, mode.size()));
+    HIP_TRY(hipMalloc(&c->d_run_start, start.size() * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&c->d_run_flag, flag.size()));
+    HIP_TRY(hipMemcpy(c->d_tile_mode, mode.data(), mode.size(), hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(c->d_run_start, start.data(), start.size() * sizeof(uint64_t), hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(c->d_run_flag, flag.data(), flag.size(), hipMemcpyHostToDevice));
+    // alignment gaps are kept at zero in every arena so that whole-arena sweeps may pass over them
+    for (const BucketL& b : L.buckets) {
+        const uint64_t end = b.arena_off + b.numel;
+        const uint64_t padded = (end + kAlignElems - 1) / kAlignElems * kAlignElems;
+        if (padded == end) continue;
+        const size_t bytes = (padded - end) * sizeof(float);
+        HIP_TRY(hipMemset(c->p + end, 0, bytes));
+        HIP_TRY(hipMemset(c->m + end, 0, bytes));
+        HIP_TRY(hipMemset(c->v + end, 0, bytes));
+        if (c->r) HIP_TRY(hipMemset(c->r + end, 0, bytes));
+    }
+    if (c->clip) {
+        c->slot_base.resize(L.buckets.size());
+        c->slot_count.resize(L.buckets.size());
+        uint64_t total = 0;
+        for (size_t b = 0; b < L.buckets.size(); ++b) {
+            c->slot_base[b] = uint32_t(total);
+            c->slot_count[b] = grid_for(L.buckets[b].numel >> 3, g_tune.fold_grid_cap);
+            total += c->slot_count[b];
+            if (total > 0x7FFFFFFFull) return SHADOW_EINVAL;
+        }
+        c->nslots = uint32_t(total);
+        HIP_TRY(hipMalloc(&c->d_partial, (total ? total : 1) * sizeof(double)));
+        HIP_TRY(hipMalloc(&c->d_coef, sizeof(float)));
+        HIP_TRY(hipMalloc(&c->d_sumsq, sizeof(double)));
+        HIP_TRY(hipMemset(c->d_partial, 0, (total ? total : 1) * sizeof(double)));
+        HIP_TRY(hipMemset(c->d_coef, 0, sizeof(float)));
+        HIP_TRY(hipMemset(c->d_sumsq, 0, sizeof(double)));
+    }
+    HIP_TRY(hipDeviceSynchronize());
+    return SHADOW_OK;
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+int32_t shadow_layout_create(shadow_layout** out, const shadow_tensor_desc* tensors, uint32_t num_tensors,
+                             const uint32_t* bucket_of_tensor, uint32_t grad_elem_bytes, uint64_t bucket_cap_bytes)
+{
+    if (!out) return SHADOW_EINVAL;
+    *out = nullptr;
+    if (!tensors || num_tensors == 0) return SHADOW_EINVAL;
+    if (grad_elem_bytes != 2 && grad_elem_bytes != 4) return SHADOW_EINVAL;
+    if (!bucket_of_tensor && bucket_cap_bytes == 0) return SHADOW_EINVAL;
+    uint64_t total = 0;
+    for (uint32_t t = 0; t < num_tensors; ++t) {
+        if (tensors[t].numel == 0 || tensors[t].weight_decay > 1 || tensors[t].reserved != 0) return SHADOW_EINVAL;
+        if (tensors[t].numel > (1ull << 48)) return SHADOW_EINVAL;
+        total += tensors[t].numel;
+        if (total > (1ull << 48)) return SHADOW_EINVAL;
+    }
+    shadow_layout* L = new (std::nothrow) shadow_layout();
+    if (!L) return SHADOW_ENOMEM;
+    try {
+        L->tensors.assign(tensors, tensors + num_tensors);
+        L->grad_elem_bytes = grad_elem_bytes;
+        if (!plan(*L, bucket_of_tensor, bucket_cap_bytes)) { delete L; return SHADOW_EINVAL; }
+    } catch (const std::bad_alloc&) {
+        delete L;
+        return SHADOW_ENOMEM;
+    }
+    *out = L;
+    return SHADOW_OK;
+}
+
+int32_t shadow_layout_destroy(shadow_layout* layout)
+{
+    delete layout;
+    return SHADOW_OK;
+}
+
+int32_t shadow_layout_num_buckets(const shadow_layout* L, uint32_t* out)
+{
+    if (!L || !out) return SHADOW_EINVAL;
+    *out = uint32_t(L->buckets.size());
+    return SHADOW_OK;
+}
+
+int32_t shadow_layout_num_params(const shadow_layout* L, uint64_t* out)
+{
+    if (!L || !out) return SHADOW_EINVAL;
+    *out = L->num_params;
+    return SHADOW_OK;
+}
+
+int32_t shadow_layout_arena_numel(const shadow_layout* L, uint64_t* out)
+{
+    if (!L || !out) return SHADOW_EINVAL;
+    *out = L->arena_numel;
+    return SHADOW_OK;
+}
+
+int32_t shadow_layout_bucket(const shadow_layout* L, uint32_t bucket, uint64_t* arena_offset, uint64_t* numel,
+                             uint32_t* num_tensors)
+{
+    if (!L) return SHADOW_EINVAL;
+    if (bucket >= L->buckets.size()) return SHADOW_EBUCKET;
+    if (arena_offset) *arena_offset = L->buckets[bucket].arena_off;
+    if (numel) *numel = L->buckets[bucket].numel;
+    if (num_tensors) *num_tensors = uint32_t(L->buckets[bucket].segs.size());
+    return SHADOW_OK;
+}
+
+int32_t shadow_layout_tensor(const shadow_layout* L, uint32_t tensor, uint32_t* bucket, uint64_t* offset_in_bucket,
+                             uint64_t* arena_offset)
+{
+    if (!L || tensor >= L->tensors.size()) return SHADOW_EINVAL;
+    const uint32_t b = L->bucket_of[tensor];
+    if (bucket) *bucket = b;
+    if (offset_in_bucket) *offset_in_bucket = L->off_in_bucket[tensor];
+    if (arena_offset) *arena_offset = L->buckets[b].arena_off + L->off_in_bucket[tensor];
+    return SHADOW_OK;
+}
+
+int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_hparams* hp, float* d_param, float* d_m,
+                    float* d_v, float* d_reduced, uint64_t start_step, void* const* streams)
+{
+    if (!out) return SHADOW_EINVAL;
+    *out = nullptr;
+    if (!layout || !hp || !d_param || !d_m || !d_v) return SHADOW_EINVAL;
+    if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) ||
+        !(hp->eps > 0.f) || !(hp->weight_decay >= 0.f) || std::isnan(hp->max_grad_norm))
+        return SHADOW_EINVAL;
+    if (hp->num_workers < 1 || hp->num_workers > SHADOW_MAX_WORKERS) return SHADOW_EINVAL;
+    if (hp->grad_dtype != SHADOW_GRAD_F32 && hp->grad_dtype != SHADOW_GRAD_BF16) return SHADOW_EINVAL;
+    if ((hp->grad_dtype == SHADOW_GRAD_BF16 ? 2u : 4u) != layout->grad_elem_bytes) return SHADOW_EINVAL;
+    if (hp->reduce_op != SHADOW_REDUCE_MEAN && hp->reduce_op != SHADOW_REDUCE_SUM) return SHADOW_EINVAL;
+    if (hp->num_streams < 1 || hp->num_streams > SHADOW_MAX_STREAMS) return SHADOW_EINVAL;
+    const bool clip = hp->max_grad_norm > 0.f;
+    if (clip != (d_reduced != nullptr)) return SHADOW_EINVAL;
+    if (!aligned(d_param, 256) || !aligned(d_m, 256) || !aligned(d_v, 256) || !aligned(d_reduced, 256)) return SHADOW_EINVAL;
+    if (d_param == d_m || d_param == d_v || d_m == d_v) return SHADOW_EINVAL;
+
+    shadow_ctx* c = new (std::nothrow) shadow_ctx();
+    if (!c) return SHADOW_ENOMEM;
+    int32_t rc = SHADOW_OK;
+    try {
+        c->lay = *layout;
+        c->hp = *hp;
+        c->p = d_param; c->m = d_m; c->v = d_v; c->r = d_reduced;
+        c->clip = clip;
+        c->completed = start_step;
+        c->arrived.assign(layout->buckets.size(), 0);
+        c->stream_dirty.assign(hp->num_streams, 0);
+        c->streams.assign(hp->num_streams, nullptr);
+        c->join_ev.assign(hp->num_streams, nullptr);
+    } catch (const std::bad_alloc&) {
+        delete c;
+        return SHADOW_ENOMEM;
+    }
+    auto fail = [&](int32_t code) { free_ctx(c); return code; };
+    if (streams) {
+        for (uint32_t s = 0; s < hp->num_streams; ++s) c->streams[s] = static_cast<hipStream_t>(streams[s]);
+    } else {
+        c->own_streams = true;
+        for (uint32_t s = 0; s < hp->num_streams; ++s) {
+            if (hipStreamCreateWithFlags(&c->streams[s], hipStreamNonBlocking) != hipSuccess) {
+                g_hip_error = "hipStreamCreateWithFlags failed";
+                return fail(SHADOW_EHIP);
+            }
+        }
+    }
+    for (uint32_t s = 0; s < hp->num_streams; ++s) {
+        if (hipEventCreateWithFlags(&c->join_ev[s], hipEventDisableTiming) != hipSuccess) {
+            g_hip_error = "hipEventCreate failed";
+            return fail(SHADOW_EHIP);
+        }
+    }
+    if (hipEventCreateWithFlags(&c->boundary_ev, hipEventDisableTiming) != hipSuccess) {
+        g_hip_error = "hipEventCreate failed";
+        return fail(SHADOW_EHIP);
+    }
+    rc = build_tables(c);
+    if (rc != SHADOW_OK) return fail(rc);
+    *out = c;
+    return SHADOW_OK;
+}
+
+int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const* d_grad_views, uint64_t step)
+{
+    if (!c || !d_grad_views) return SHADOW_EINVAL;
+    if (c->poisoned) return SHADOW_EHIP;
+    if (bucket_id >= c->lay.buckets.size()) return SHADOW_EBUCKET;
+    if (step != c->completed + 1) return SHADOW_ESTEP;
+    if (c->arrived[bucket_id]) return SHADOW_EDUP;
+    const uint32_t W = c->hp.num_workers;
+    GradViews gv{};
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!d_grad_views[w] || !aligned(d_grad_views[w], 16)) return SHADOW_EINVAL;
+        gv.ptr[w] = d_grad_views[w];
+    }
+    // ---- nothing above changed any state; from here on work is enqueued ----
+    const BucketL& b = c->lay.buckets[bucket_id];
+    const uint32_t S = uint32_t(c->streams.size());
+    const uint32_t sid = bucket_id % S;
+    hipStream_t st = c->streams[sid];
+    auto hip_fail = [&](const char* what, hipError_t e) {
+        g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+        c->poisoned = true;
+        return int32_t(SHADOW_EHIP);
+    };
+    hipError_t e;
+    if (c->arrived_count == 0) {
+        if (c->sc_step != step) { compute_scalars(c->hp, step, c->sc); c->sc_step = step; }
+        if (c->boundary_pending) {
+            // work of the previous iteration boundary (whole-arena update, snapshot copies) ran on
+            // stream 0; every other stream orders behind it before touching the arenas again
+            for (uint32_t s = 1; s < S; ++s)
+                if ((e = hipStreamWaitEvent(c->streams[s], c->boundary_ev, 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
+            c->boundary_pending = false;
+        }
+    }
+    const WdMap map = wd_map(c);
+    {
+        ProfScope ps(c, c->clip ? SHADOW_K_FOLD_SUMSQ : SHADOW_K_FOLD_ADAMW, st);
+        if (ps.rc != SHADOW_OK) { c->poisoned = true; return ps.rc; }
+        if (c->hp.grad_dtype == SHADOW_GRAD_BF16) dispatch_fold<true>(c, gv, b, bucket_id, st, map);
+        else dispatch_fold<false>(c, gv, b, bucket_id, st, map);
+        if ((e = hipGetLastError()) != hipSuccess) return hip_fail("fold kernel launch", e);
+        if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
+    }
+    c->stream_dirty[sid] = 1;
+    c->arrived[bucket_id] = 1;
+    c->arrived_count++;
+    if (c->arrived_count == c->lay.buckets.size()) {
+        if (c->clip) {
+            int32_t rc = join_to_stream0(c);
+            if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+            hipStream_t s0 = c->streams[0];
+            {
+                ProfScope ps(c, SHADOW_K_NORM, s0);
+                if (ps.rc != SHADOW_OK) { c->poisoned = true; return ps.rc; }
+                k_norm_finalize<<<1, 1024, 0, s0>>>(c->d_partial, c->nslots, c->hp.max_grad_norm, c->d_coef, c->d_sumsq);
+                if ((e = hipGetLastError()) != hipSuccess) return hip_fail("norm kernel launch", e);
+                if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
+            }
+            {
+                ProfScope ps(c, SHADOW_K_ADAMW, s0);
+                if (ps.rc != SHADOW_OK) { c->poisoned = true; return ps.rc; }
+                const uint64_t nvec = c->lay.arena_numel >> 3;
+                k_adamw<<<grid_for(nvec, g_tune.adamw_grid_cap), kBlock, 0, s0>>>(c->r, c->p, c->m, c->v, nvec, c->d_coef, map, c->sc);
+                if ((e = hipGetLastError()) != hipSuccess) return hip_fail("adamw kernel launch", e);
+                if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
+            }
+            c->stream_dirty[0] = 1;
+            rc = mark_boundary(c);
+            if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+        }
+        std::fill(c->arrived.begin(), c->arrived.end(), uint8_t(0));
+        c->arrived_count = 0;
+        c->completed = step;
+    }
+    return SHADOW_OK;
+}
+
+int32_t shadow_snapshot(shadow_ctx* c, float* dst_param, float* dst_m, float* dst_v, uint64_t* out_step)
+{
+    if (!c) return SHADOW_EINVAL;
+    if (c->poisoned) return SHADOW_EHIP;
+    if (c->arrived_count != 0) return SHADOW_EBUSY;
+    int32_t rc = join_to_stream0(c);
+    if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+    const size_t bytes = c->lay.arena_numel * sizeof(float);
+    hipStream_t s0 = c->streams[0];
+    if (dst_param) HIP_TRY(hipMemcpyAsync(dst_param, c->p, bytes, hipMemcpyDefault, s0));
+    if (dst_m) HIP_TRY(hipMemcpyAsync(dst_m, c->m, bytes, hipMemcpyDefault, s0));
+    if (dst_v) HIP_TRY(hipMemcpyAsync(dst_v, c->v, bytes, hipMemcpyDefault, s0));
+    rc = mark_boundary(c);
+    if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+    if (out_step) *out_step = c->completed;
+    return SHADOW_OK;
+}
+
+int32_t shadow_sync(shadow_ctx* c)
+{
+    if (!c) return SHADOW_EINVAL;
+    for (hipStream_t s : c->streams) HIP_TRY(hipStreamSynchronize(s));
+    return SHADOW_OK;
+}
+
+int32_t shadow_destroy(shadow_ctx* c)
+{
+    if (!c) return SHADOW_OK;
+    for (hipStream_t s : c->streams) (void)hipStreamSynchronize(s);
+    free_ctx(c);
+    return SHADOW_OK;
+}
+
+int32_t shadow_step(const shadow_ctx* c, uint64_t* completed_step, uint32_t* buckets_pending)
+{
+    if (!c) return SHADOW_EINVAL;
+    if (completed_step) *completed_step = c->completed;
+    if (buckets_pending) *buckets_pending = c->arrived_count ? uint32_t(c->lay.buckets.size()) - c->arrived_count : 0;
+    return SHADOW_OK;
+}
+
+int32_t shadow_bucket_stream(const shadow_ctx* c, uint32_t bucket_id, void** out_stream)
+{
+    if (!c || !out_stream) return SHADOW_EINVAL;
+    if (bucket_id >= c->lay.buckets.size()) return SHADOW_EBUCKET;
+    *out_stream = c->streams[bucket_id % c->streams.size()];
+    return SHADOW_OK;
+}
+
+int32_t shadow_clip_state(shadow_ctx* c, float* out_coef, double* out_sumsq)
+{
+    if (!c || !c->clip) return SHADOW_EINVAL;
+    int32_t rc = shadow_sync(c);
+    if (rc != SHADOW_OK) return rc;
+    if (out_coef) HIP_TRY(hipMemcpy(out_coef, c->d_coef, sizeof(float), hipMemcpyDeviceToHost));
+    if (out_sumsq) HIP_TRY(hipMemcpy(out_sumsq, c->d_sumsq, sizeof(double), hipMemcpyDeviceToHost));
+    return SHADOW_OK;
+}
+
+int32_t shadow_set_lr(shadow_ctx* c, float lr)
+{
+    if (!c || !(lr >= 0.f)) return SHADOW_EINVAL;
+    if (c->arrived_count != 0) return SHADOW_EBUSY;
+    c->hp.lr = lr;
+    c->sc_step = 0;
+    return SHADOW_OK;
+}
+
+int32_t shadow_profile_enable(shadow_ctx* c, int32_t on)
+{
+    if (!c) return SHADOW_EINVAL;
+    c->profile = on != 0;
+    return SHADOW_OK;
+}
+
+int32_t shadow_profile_read(shadow_ctx* c, uint32_t kind, uint64_t* launches, double* total_ms)
+{
+    if (!c || kind >= SHADOW_K_COUNT) return SHADOW_EINVAL;
+    int32_t rc = shadow_sync(c);
+    if (rc != SHADOW_OK) return rc;
+    double total = 0.0;
+    uint64_t n = 0;
+    for (auto& sp : c->spans[kind]) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
+        total += ms;
+        ++n;
+        c->ev_pool.push_back(sp.a);
+        c->ev_pool.push_back(sp.b);
+    }
+    c->spans[kind].clear();
+    if (launches) *launches = n;
+    if (total_ms) *total_ms = total;
+    return SHADOW_OK;
+}
+
+int32_t shadow_copy_probe(void* d_dst, const void* d_src, uint64_t bytes, void* stream)
+{
+    if (!d_dst || !d_src || (bytes & 15) || !aligned(d_dst, 16) || !aligned(d_src, 16)) return SHADOW_EINVAL;
+    const uint64_t n16 = bytes >> 4;
+    if (n16 == 0) return SHADOW_OK;
+    k_copy<<<grid_for(n16, g_tune.adamw_grid_cap), kBlock, 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<const u32x4*>(d_src), static_cast<u32x4*>(d_dst), n16);
+    HIP_TRY(hipGetLastError());
+    return SHADOW_OK;
+}
+
+const char* shadow_strerror(int32_t status)
+{
+    switch (status) {
+        case SHADOW_OK: return "ok";
+        case SHADOW_EINVAL: return "invalid argument";
+        case SHADOW_EBUCKET: return "bucket id out of range";
+        case SHADOW_EDUP: return "bucket already applied in this iteration";
+        case SHADOW_ESTEP: return "step is not the last completed step + 1";
+        case SHADOW_EBUSY: return "an iteration is partly applied";
+        case SHADOW_EHIP: return "HIP runtime failure";
+        case SHADOW_ENOMEM: return "out of memory";
+        default: return "unknown status";
+    }
+}
+
+const char* shadow_last_hip_error(void) { return g_hip_error.c_str(); }
+
+int32_t shadow_set_tunable(const char* name, int64_t value)
+{
+    if (!name || value < 1 || value > (1 << 30)) return SHADOW_EINVAL;
+    if (!std::strcmp(name, "fold_grid_cap")) g_tune.fold_grid_cap = value;
+    else if (!std::strcmp(name, "adamw_grid_cap")) g_tune.adamw_grid_cap = value;
+    else return SHADOW_EINVAL;
+    return SHADOW_OK;
+}
+
+}  // extern "C"

@@ -17,6 +17,7 @@ from .rng import (  # noqa: F401
     bf16_bits_to_f32,
     grad_values,
     param_values,
+    tiled,
     arrival_order,
 )
 from .workloads import Workload, TensorSpec, get_workload, WORKLOADS  # noqa: F401

@@ -156,6 +156,11 @@ def param_values(seed: int, idx: torch.Tensor, sigma: float = 0.02, period: Opti
     return normal_f32(base, _periodic(idx, period), sigma)
 
 
+def tiled(tile: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
+    """Values of a periodic input at indices ``idx`` given one period ``tile`` (= values at 0..period-1)."""
+    return tile[idx % tile.numel()]
+
+
 def arrival_order(seed: int, step: int, num_buckets: int) -> list:
     """Seeded Fisher-Yates shuffle of bucket ids for one step."""
     base = stream_base(seed, STREAM_ARRIVAL, step)

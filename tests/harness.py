@@ -1,0 +1,247 @@
+"""Shared plumbing of the GPU parity tests: inputs, arenas, comparison.
+
+Inputs come from ``synth`` only.  Small cases use a distinct value per element;
+cases at model size use tiled inputs (element e takes the tile's value at
+e mod L, L prime) so that the oracle can obtain the global gradient norm from
+one tile with multiplicities and then check sampled elements and whole sampled
+buckets exactly.  Tiles are always generated on the CPU and uploaded, so both
+sides see the same bits whatever the device's float arithmetic does.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2507_13522_amd as sh
+import synth
+
+TILE_PERIOD = 1_000_003          # prime
+
+
+class Inputs:
+    """Gradient views and initial parameters of a workload, on CPU (numpy) and on the GPU (torch)."""
+
+    def __init__(self, wl: synth.Workload, period: Optional[int] = None, device: Optional[str] = None):
+        self.wl, self.period, self.device = wl, period, device
+        self._tiles: Dict = {}
+        self._tiles_dev: Dict = {}
+
+    # -- CPU ---------------------------------------------------------------
+    def _tile(self, key):
+        if key not in self._tiles:
+            idx = torch.arange(self.period, dtype=torch.int64)
+            if key == "param":
+                t = synth.param_values(self.wl.seed, idx, self.wl.param_sigma)
+            else:
+                step, w = key
+                t = synth.grad_values(self.wl.seed, step, w, idx, self.wl.grad_dist, self.wl.grad_sigma, self.wl.grad_dtype)
+            self._tiles[key] = t
+            if len(self._tiles) > 80:
+                self._tiles.pop(next(iter(self._tiles)))
+        return self._tiles[key]
+
+    def grad_at(self, step: int, w: int, idx: torch.Tensor) -> torch.Tensor:
+        """CPU tensor (float32, or int16 bfloat16 patterns) at logical element indices idx."""
+        if self.period:
+            return synth.tiled(self._tile((step, w)), idx)
+        return synth.grad_values(self.wl.seed, step, w, idx, self.wl.grad_dist, self.wl.grad_sigma, self.wl.grad_dtype)
+
+    def param_at(self, idx: torch.Tensor) -> torch.Tensor:
+        if self.period:
+            return synth.tiled(self._tile("param"), idx)
+        return synth.param_values(self.wl.seed, idx, self.wl.param_sigma)
+
+    def grad_np(self, step: int, w: int, start: int, n: int) -> np.ndarray:
+        t = self.grad_at(step, w, torch.arange(start, start + n, dtype=torch.int64))
+        a = t.numpy()
+        return a.view(np.uint16).copy() if self.wl.grad_dtype == "bf16" else a.copy()
+
+    def param_np(self, start: int, n: int) -> np.ndarray:
+        return self.param_at(torch.arange(start, start + n, dtype=torch.int64)).numpy().copy()
+
+    # -- GPU ---------------------------------------------------------------
+    def _tile_dev(self, key):
+        if key not in self._tiles_dev:
+            self._tiles_dev[key] = self._tile(key).to(self.device)
+            if len(self._tiles_dev) > 80:
+                self._tiles_dev.pop(next(iter(self._tiles_dev)))
+        return self._tiles_dev[key]
+
+    def fill_grad_dev(self, out: torch.Tensor, step: int, w: int, start: int) -> None:
+        n = out.numel()
+        if self.period:
+            idx = torch.arange(start, start + n, dtype=torch.int64, device=self.device)
+            torch.index_select(self._tile_dev((step, w)), 0, idx % self.period, out=out)
+        else:
+            out.copy_(self.grad_at(step, w, torch.arange(start, start + n, dtype=torch.int64)))
+
+    def fill_param_dev(self, out: torch.Tensor, start: int) -> None:
+        n = out.numel()
+        if self.period:
+            idx = torch.arange(start, start + n, dtype=torch.int64, device=self.device)
+            torch.index_select(self._tile_dev("param"), 0, idx % self.period, out=out)
+        else:
+            out.copy_(self.param_at(torch.arange(start, start + n, dtype=torch.int64)))
+
+
+def oracle_layout(wl: synth.Workload) -> oracle.Layout:
+    return oracle.build_layout([(t.numel, t.weight_decay) for t in wl.tensors], wl.grad_bytes, wl.bucket_cap_bytes,
+                               wl.explicit_buckets)
+
+
+def oracle_hparams(wl: synth.Workload, mean: bool = True) -> oracle.HParams:
+    return oracle.HParams(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay,
+                          max_grad_norm=wl.max_grad_norm, mean=mean)
+
+
+def lib_layout(wl: synth.Workload) -> sh.Layout:
+    return sh.Layout([(t.numel, t.weight_decay) for t in wl.tensors], wl.grad_bytes, wl.bucket_cap_bytes,
+                     wl.explicit_buckets)
+
+
+def lib_hparams(wl: synth.Workload, num_streams: int = 2, mean: bool = True) -> sh.HParams:
+    return sh.HParams(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay,
+                      max_grad_norm=wl.max_grad_norm, num_workers=wl.num_workers,
+                      grad_dtype=sh.GRAD_BF16 if wl.grad_dtype == "bf16" else sh.GRAD_F32,
+                      reduce_op=sh.REDUCE_MEAN if mean else sh.REDUCE_SUM, num_streams=num_streams)
+
+
+def assert_layouts_agree(ol: oracle.Layout, ll: sh.Layout) -> None:
+    assert ll.num_buckets == len(ol.buckets) and ll.num_params == ol.num_params
+    prev_end = 0
+    for b, ob in enumerate(ol.buckets):
+        off, n, nt = ll.bucket(b)
+        assert n == ob.numel and nt == len(ob.segments) and off % 64 == 0 and off >= prev_end and off - prev_end < 64
+        prev_end = off + n
+        for s in ob.segments:
+            tb, tob, toa = ll.tensor(s.tensor)
+            assert (tb, tob, toa) == (b, s.offset, off + s.offset)
+    assert ll.arena_numel == (prev_end + 63) // 64 * 64
+
+
+class GpuShadow:
+    """The library on cuda:0 over torch-allocated arenas, with every bucket's W views resident."""
+
+    def __init__(self, wl: synth.Workload, inputs: Inputs, num_streams: int = 2, mean: bool = True,
+                 torch_streams: bool = False, resident_grads: bool = True, init_from=None, start_step: int = 0):
+        assert torch.cuda.is_available()
+        self.wl, self.inputs = wl, inputs
+        self.dev = torch.device("cuda:0")
+        inputs.device = self.dev
+        self.layout = lib_layout(wl)
+        L = self.layout
+        self.buckets = [L.bucket(b) for b in range(L.num_buckets)]
+        self.logical_start, acc = [], 0
+        for off, n, _ in self.buckets:
+            self.logical_start.append(acc)
+            acc += n
+        A = L.arena_numel
+        self.p = torch.empty(A, dtype=torch.float32, device=self.dev)
+        self.m = torch.zeros(A, dtype=torch.float32, device=self.dev)
+        self.v = torch.zeros(A, dtype=torch.float32, device=self.dev)
+        self.r = torch.empty(A, dtype=torch.float32, device=self.dev) if wl.max_grad_norm > 0 else None
+        if init_from is None:
+            for (off, n, _), ls in zip(self.buckets, self.logical_start):
+                inputs.fill_param_dev(self.p[off:off + n], ls)
+        else:
+            self.p.copy_(init_from[0]); self.m.copy_(init_from[1]); self.v.copy_(init_from[2])
+        gdt = torch.int16 if wl.grad_dtype == "bf16" else torch.float32
+        self.grads = None
+        if resident_grads:
+            self.grads = [torch.empty(A, dtype=gdt, device=self.dev) for _ in range(wl.num_workers)]
+        self.gdt = gdt
+        self.hp = lib_hparams(wl, num_streams, mean)
+        self._tstreams = [torch.cuda.Stream(device=self.dev) for _ in range(num_streams)] if torch_streams else None
+        torch.cuda.synchronize()
+        self.ctx = sh.Shadow(L, self.hp, self.p.data_ptr(), self.m.data_ptr(), self.v.data_ptr(),
+                             self.r.data_ptr() if self.r is not None else None, start_step,
+                             [s.cuda_stream for s in self._tstreams] if self._tstreams else None)
+        self._views = None
+        if resident_grads:
+            self._views = [self.ctx.views_array([g[off:off + n].data_ptr() for g in self.grads]) for off, n, _ in self.buckets]
+
+    def fill_grads(self, step: int, buckets: Optional[Sequence[int]] = None) -> None:
+        for b in (range(len(self.buckets)) if buckets is None else buckets):
+            off, n, _ = self.buckets[b]
+            for w in range(self.wl.num_workers):
+                self.inputs.fill_grad_dev(self.grads[w][off:off + n], step, w, self.logical_start[b])
+        torch.cuda.synchronize()
+
+    def apply_step(self, step: int, order: Optional[Sequence[int]] = None) -> None:
+        for b in (range(len(self.buckets)) if order is None else order):
+            self.ctx.apply_bucket(b, self._views[b], step)
+
+    def run_step(self, step: int, order: Optional[Sequence[int]] = None) -> None:
+        self.fill_grads(step)
+        self.apply_step(step, order)
+        self.ctx.sync()
+
+    def bucket_state(self, b: int):
+        off, n, _ = self.buckets[b]
+        self.ctx.sync()
+        return tuple(x[off:off + n].cpu().numpy() for x in (self.p, self.m, self.v))
+
+    def close(self) -> None:
+        self.ctx.destroy()
+
+
+def run_oracle_full(wl: synth.Workload, inputs: Inputs, steps: int, orders=None, mean: bool = True, precision: str = "f32",
+                    on_step=None) -> oracle.OracleShadow:
+    """Whole-model oracle run (small and medium workloads)."""
+    lay = oracle_layout(wl)
+    starts = lay.logical_starts()
+    params = [inputs.param_np(s, b.numel) for s, b in zip(starts, lay.buckets)]
+    orc = oracle.OracleShadow(lay, oracle_hparams(wl, mean), params, precision=precision)
+    for t in range(1, steps + 1):
+        grads = {b: [inputs.grad_np(t, w, starts[b], lay.buckets[b].numel) for w in range(wl.num_workers)]
+                 for b in range(len(lay.buckets))}
+        orc.step(grads)
+        if on_step:
+            on_step(t, orc)
+    return orc
+
+
+@dataclass
+class Diff:
+    max_rel: float
+    n_bits_differ: int
+    max_ulp: int
+
+    def __str__(self) -> str:
+        return f"max_rel={self.max_rel:.3e} bits_differ={self.n_bits_differ} max_ulp={self.max_ulp}"
+
+
+def diff(got: np.ndarray, ref: np.ndarray) -> Diff:
+    """max |got-ref| / max(|ref|, 1e-30), number of elements whose bits differ, largest distance in ulps."""
+    got = np.ascontiguousarray(got, dtype=np.float32)
+    ref = np.ascontiguousarray(ref, dtype=np.float32)
+    assert got.shape == ref.shape
+    if got.size == 0:
+        return Diff(0.0, 0, 0)
+    gb, rb = got.view(np.int32).astype(np.int64), ref.view(np.int32).astype(np.int64)
+    nd = int(np.count_nonzero(gb != rb))
+    if nd == 0:
+        return Diff(0.0, 0, 0)
+    g64, r64 = got.astype(np.float64), ref.astype(np.float64)
+    rel = float(np.max(np.abs(g64 - r64) / np.maximum(np.abs(r64), 1e-30)))
+    mono = lambda x: np.where(x < 0, -(x & 0x7FFFFFFF), x)
+    ulp = int(np.max(np.abs(mono(gb) - mono(rb))))
+    return Diff(rel, nd, ulp)
+
+
+REL_TOL = 1e-6      # max relative error on param, m and v
+
+
+def assert_state_matches(got, ref, what: str, exact: bool = True) -> List[Diff]:
+    out = []
+    for name, g, r in zip("pmv", got, ref):
+        d = diff(g, r)
+        out.append(d)
+        assert d.max_rel <= REL_TOL, f"{what} {name}: {d}"
+        if exact:
+            assert d.n_bits_differ == 0, f"{what} {name}: expected identical bits, {d}"
+    return out

@@ -1,0 +1,339 @@
+"""HIP path vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2507_13522_amd as sh
+from paper_2507_13522_amd import binding
+import synth
+from harness import (GpuShadow, Inputs, assert_layouts_agree, assert_state_matches, diff, lib_layout, oracle_layout,
+                     run_oracle_full, REL_TOL)
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def custom(name, sizes_flags, W, dtype, clip=0.0, cap=1 << 16, steps=3, dist="normal", sigma=1e-3, wd=0.01, explicit=None,
+           random_arrival=False, lr=1e-3):
+    ts = [synth.TensorSpec(f"t{i}", n, f) for i, (n, f) in enumerate(sizes_flags)]
+    return synth.Workload(name, ts, num_workers=W, grad_dtype=dtype, grad_dist=dist, grad_sigma=sigma, steps=steps,
+                          max_grad_norm=clip, bucket_cap_bytes=cap, explicit_buckets=explicit, weight_decay=wd,
+                          random_arrival=random_arrival, lr=lr)
+
+
+def check_against_oracle(wl, steps=None, num_streams=2, mean=True, every_step=True, exact=True, torch_streams=False):
+    """Run both sides on the same inputs and compare param, m, v of every bucket."""
+    steps = steps or wl.steps
+    inp = Inputs(wl)
+    assert_layouts_agree(oracle_layout(wl), lib_layout(wl))
+    g = GpuShadow(wl, inp, num_streams=num_streams, mean=mean, torch_streams=torch_streams)
+    worst = {}
+
+    def on_step(t, orc):
+        order = synth.arrival_order(wl.seed, t, len(g.buckets)) if wl.random_arrival else None
+        g.run_step(t, order)
+        if every_step or t == steps:
+            for b in range(len(g.buckets)):
+                ds = assert_state_matches(g.bucket_state(b), (orc.p[b], orc.m[b], orc.v[b]), f"{wl.name} step {t} bucket {b}", exact)
+                for k, d in zip("pmv", ds):
+                    worst[k] = max(worst.get(k, 0.0), d.max_rel)
+            if wl.max_grad_norm > 0:
+                c, S = g.ctx.clip_state()
+                assert np.float32(c) == orc.last_coef, (c, orc.last_coef)
+                assert abs(S - orc.last_sumsq) <= 1e-12 * orc.last_sumsq
+
+    run_oracle_full(wl, inp, steps, mean=mean, on_step=on_step)
+    assert g.ctx.step() == (steps, 0)
+    g.close()
+    return worst
+
+
+def test_tiny_config_every_step():
+    """Config 'tiny': 1,048,576 params in 4 buckets, W=4 fp32 gradients, 10 steps, no clipping."""
+    say("case tiny")
+    wl = synth.get_workload("tiny")
+    worst = check_against_oracle(wl)
+    say("tiny worst rel", worst)
+
+
+RAGGED = [(5000, True), (33, False), (70001, True), (1, False), (64, True), (12345, False), (300007, True), (999, True),
+          (2048, False), (77777, True), (7, True), (3, False), (5, True), (1024, True), (8, False)]
+
+
+@pytest.mark.parametrize("W,dtype", [(3, "bf16"), (8, "bf16"), (5, "f32")])
+def test_ragged_clip_random_arrival(W, dtype):
+    """Several tiles, ragged tails, flags changing inside a vector, clipping active, shuffled bucket arrival."""
+    say("case ragged", W, dtype)
+    wl = custom("ragged", RAGGED, W, dtype, clip=0.01, cap=200_000, steps=5, random_arrival=True)
+    check_against_oracle(wl, num_streams=3)
+
+
+@pytest.mark.parametrize("W", [1, 2, 4, 6, 8, 16, 32, 64])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("clip", [0.0, 0.005])
+def test_worker_counts(W, dtype, clip):
+    say("case W", W, dtype, clip)
+    wl = custom("wsweep", [(20011, True), (4099, False), (9000, True), (17, False)], W, dtype, clip=clip, cap=30_000, steps=2)
+    check_against_oracle(wl, num_streams=2)
+
+
+def test_sum_reduce_and_student_t():
+    say("case sum/t3")
+    wl = custom("sum", RAGGED[:8], 4, "bf16", clip=0.05, cap=150_000, steps=3, dist="t3")
+    check_against_oracle(wl, mean=False)
+    check_against_oracle(wl, mean=True)
+
+
+def test_degenerate_buckets():
+    """Buckets smaller than one vector, a one-element model, sizes that are exact multiples of the tile."""
+    say("case degenerate")
+    for sizes in ([(1, True)], [(7, False)], [(8, True)], [(3, True), (2, False), (1, True)], [(1024, True), (1024, False)],
+                  [(2048, True)], [(2049, True)], [(65536, False), (5, True)]):
+        for clip in (0.0, 1e-4):
+            wl = custom("degenerate", sizes, 2, "bf16", clip=clip, cap=2048, steps=2)
+            check_against_oracle(wl, num_streams=1)
+
+
+def test_borrowed_torch_streams():
+    say("case torch streams")
+    wl = custom("tstreams", RAGGED, 4, "bf16", clip=0.01, cap=200_000, steps=3)
+    check_against_oracle(wl, num_streams=4, torch_streams=True)
+
+
+def test_clip_inactive_equals_no_clip():
+    """With the norm below the threshold c == 1 and the two-pass path gives the bits of the fused path."""
+    say("case clip inactive")
+    sizes = RAGGED[:9]
+    a = custom("noclip", sizes, 4, "bf16", clip=0.0, cap=150_000, steps=3)
+    b = custom("clip", sizes, 4, "bf16", clip=1e6, cap=150_000, steps=3)
+    ga, gb = GpuShadow(a, Inputs(a)), GpuShadow(b, Inputs(b))
+    for t in range(1, 4):
+        ga.run_step(t)
+        gb.run_step(t)
+        assert gb.ctx.clip_state()[0] == 1.0
+    assert torch.equal(ga.p, gb.p) and torch.equal(ga.m, gb.m) and torch.equal(ga.v, gb.v)
+    ga.close(); gb.close()
+
+
+def test_ieee_divide_sqrt_denormals_bruteforce():
+    """One AdamW step on 2^22 elements whose p, m, v, g span the whole float range (denormals,
+    huge and tiny magnitudes): divide, sqrt and every multiply/add must round as on the host."""
+    say("case ieee bruteforce")
+    n = 1 << 22
+    rng = np.random.default_rng(99)
+
+    def wide(signed=True, emin=-149, emax=60):
+        e = rng.uniform(emin, emax, n)
+        x = np.exp2(e) * rng.uniform(1.0, 2.0, n)
+        if signed:
+            x = x * rng.choice([-1.0, 1.0], n)
+        return x.astype(np.float32)
+
+    p0, m0, v0, g0 = wide(), wide(), wide(signed=False, emin=-149, emax=40), wide(emin=-140, emax=15)
+    v0[:1000] = 0.0
+    g0[500:1500] = 0.0
+    m0[2000:3000] = 0.0
+    wl = custom("ieee", [(n // 2, True), (n // 2, False)], 1, "f32", clip=0.0, cap=1 << 30, steps=1)
+    hp = oracle.HParams(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay)
+    for t in (1, 7, 1000):
+        lay = lib_layout(wl)
+        assert lay.num_buckets == 1 and lay.arena_numel == n
+        dev = torch.device("cuda:0")
+        p, m, v = (torch.from_numpy(x.copy()).to(dev) for x in (p0, m0, v0))
+        gdev = torch.from_numpy(g0.copy()).to(dev)
+        torch.cuda.synchronize()
+        ctx = sh.Shadow(lay, sh.HParams(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay,
+                                        max_grad_norm=0.0, num_workers=1, grad_dtype=sh.GRAD_F32, reduce_op=sh.REDUCE_MEAN,
+                                        num_streams=1), p.data_ptr(), m.data_ptr(), v.data_ptr(), None, t - 1)
+        ctx.apply_bucket(0, [gdev.data_ptr()], t)
+        ctx.sync()
+        rp, rm, rv = p0.copy(), m0.copy(), v0.copy()
+        # bucket order is last tensor first: the masked half comes first
+        h = n // 2
+        oracle.adamw_f32(rp[:h], rm[:h], rv[:h], g0[:h], False, hp, t)
+        oracle.adamw_f32(rp[h:], rm[h:], rv[h:], g0[h:], True, hp, t)
+        for name, got, ref in (("p", p, rp), ("m", m, rm), ("v", v, rv)):
+            got = got.cpu().numpy()
+            same = (got.view(np.uint32) == ref.view(np.uint32)) | (np.isnan(got) & np.isnan(ref))
+            assert same.all(), f"t={t} {name}: {np.count_nonzero(~same)} elements differ, first {np.flatnonzero(~same)[:5]}"
+        ctx.destroy()
+
+
+def test_order_partition_and_stream_invariance():
+    """Functional optimizer (section 4.2.4): the result does not depend on bucket arrival order,
+    on how tensors are split into buckets, or on how many streams carry the buckets."""
+    say("case invariance")
+    sizes = RAGGED
+    T = len(sizes)
+    results = []
+    for label, cap, explicit, streams, shuffle in [("base", 200_000, None, 1, False), ("shuffled", 200_000, None, 4, True),
+                                                   ("one bucket", 1 << 30, None, 2, False),
+                                                   ("bucket per tensor", 0, list(range(T - 1, -1, -1)), 3, True)]:
+        wl = custom("inv", sizes, 4, "bf16", clip=0.0, cap=cap, steps=3, explicit=explicit)
+        g = GpuShadow(wl, Inputs(wl), num_streams=streams)
+        # note: logical element order differs between partitions, so inputs are addressed per TENSOR here
+        per_tensor = {}
+        for t in range(T):
+            b, ob, oa = g.layout.tensor(t)
+            per_tensor[t] = (b, ob, oa)
+        base = np.cumsum([0] + [n for n, _ in sizes])
+        inp = Inputs(wl)
+        for t in range(T):
+            b, ob, oa = per_tensor[t]
+            n = sizes[t][0]
+            g.p[oa:oa + n].copy_(inp.param_at(torch.arange(base[t], base[t] + n)))
+        torch.cuda.synchronize()
+        for step in range(1, 4):
+            for t in range(T):
+                b, ob, oa = per_tensor[t]
+                n = sizes[t][0]
+                for w in range(4):
+                    g.grads[w][oa:oa + n].copy_(inp.grad_at(step, w, torch.arange(base[t], base[t] + n)))
+            torch.cuda.synchronize()
+            order = synth.arrival_order(5, step, len(g.buckets)) if shuffle else None
+            g.apply_step(step, order)
+            g.ctx.sync()
+        out = []
+        for t in range(T):
+            oa, n = per_tensor[t][2], sizes[t][0]
+            out.append(tuple(x[oa:oa + n].cpu().numpy().copy() for x in (g.p, g.m, g.v)))
+        results.append((label, out))
+        g.close()
+    for label, out in results[1:]:
+        for t in range(T):
+            for k in range(3):
+                assert np.array_equal(out[t][k].view(np.uint32), results[0][1][t][k].view(np.uint32)), (label, t, "pmv"[k])
+
+
+def test_clip_arrival_order_invariance():
+    say("case clip order invariance")
+    wl = custom("inv-clip", RAGGED, 8, "bf16", clip=0.01, cap=100_000, steps=3)
+    outs = []
+    for shuffle, streams in [(False, 1), (True, 4), (True, 2)]:
+        g = GpuShadow(wl, Inputs(wl), num_streams=streams)
+        for step in range(1, 4):
+            g.run_step(step, synth.arrival_order(11 + streams, step, len(g.buckets)) if shuffle else None)
+        outs.append((g.p.clone(), g.m.clone(), g.v.clone(), g.ctx.clip_state()))
+        g.close()
+    for o in outs[1:]:
+        assert o[3] == outs[0][3]
+        assert all(torch.equal(a, b) for a, b in zip(o[:3], outs[0][:3]))
+
+
+def test_snapshot_restore_every_second_step():
+    """Section 6.5 protocol: an interrupted run that restores the shadow's state every second
+    iteration is identical to the uninterrupted run."""
+    say("case snapshot/restore")
+    wl = custom("restore", RAGGED, 4, "bf16", clip=0.01, cap=200_000, steps=6)
+    inp = Inputs(wl)
+    straight = GpuShadow(wl, inp)
+    for t in range(1, 7):
+        straight.run_step(t)
+    g = GpuShadow(wl, inp)
+    A = g.layout.arena_numel
+    host = [torch.empty(A, dtype=torch.float32).pin_memory() for _ in range(3)]
+    for t in range(1, 7):
+        g.run_step(t)
+        if t % 2 == 0:
+            st = g.ctx.snapshot(*(h.data_ptr() for h in host))
+            g.ctx.sync()
+            assert st == t
+            g.close()
+            g = GpuShadow(wl, inp, init_from=[h.clone() for h in host], start_step=t)
+    for a, b in zip((g.p, g.m, g.v), (straight.p, straight.m, straight.v)):
+        assert torch.equal(a, b)
+    # device-side snapshot equals the arenas, and its step is the completed one
+    dst = [torch.empty(A, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    assert g.ctx.snapshot(*(d.data_ptr() for d in dst)) == 6
+    g.ctx.sync()
+    assert all(torch.equal(a, b) for a, b in zip(dst, (g.p, g.m, g.v)))
+    g.close(); straight.close()
+
+
+def test_snapshot_orders_before_next_iteration():
+    """A snapshot enqueued at a boundary holds that iteration's state even if the next iteration is enqueued right behind it."""
+    say("case snapshot ordering")
+    wl = custom("snap-order", [(3_000_001, True), (2_000_003, False), (1_000_000, True)], 4, "bf16", clip=0.01, cap=1 << 22, steps=2)
+    g = GpuShadow(wl, Inputs(wl), num_streams=3)
+    A = g.layout.arena_numel
+    g.run_step(1)
+    want = [x.clone() for x in (g.p, g.m, g.v)]
+    dst = [torch.empty(A, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    g.fill_grads(2)
+    g.ctx.snapshot(*(d.data_ptr() for d in dst))
+    g.apply_step(2)
+    g.ctx.sync()
+    assert all(torch.equal(a, b) for a, b in zip(dst, want))
+    assert not torch.equal(g.p, want[0])
+    g.close()
+
+
+def test_exactly_once_errors_leave_state_untouched():
+    """Section 4.1: duplication or loss of a bucket must not go unnoticed."""
+    say("case errors")
+    wl = custom("errors", [(5000, True), (6000, False), (7000, True)], 2, "bf16", clip=0.01, cap=12_000, steps=2)
+    g = GpuShadow(wl, Inputs(wl))
+    B = len(g.buckets)
+    assert B >= 2
+    g.fill_grads(1)
+    before = [x.clone() for x in (g.p, g.m, g.v)]
+    v0 = g._views[0]
+    assert g.ctx.try_apply_bucket(B, v0, 1) == binding.EBUCKET
+    assert g.ctx.try_apply_bucket(0, v0, 2) == binding.ESTEP
+    assert g.ctx.try_apply_bucket(0, v0, 0) == binding.ESTEP
+    off, n, _ = g.buckets[0]
+    misaligned = g.ctx.views_array([g.grads[0][off + 1:].data_ptr(), g.grads[1][off:].data_ptr()])
+    assert g.ctx.try_apply_bucket(0, misaligned, 1) == binding.EINVAL
+    assert g.ctx.try_apply_bucket(0, g.ctx.views_array([g.grads[0][off:].data_ptr(), 0]), 1) == binding.EINVAL
+    g.ctx.sync()
+    assert all(torch.equal(a, b) for a, b in zip(before, (g.p, g.m, g.v))) and g.ctx.step() == (0, 0)
+    assert g.ctx.try_apply_bucket(0, v0, 1) == binding.OK
+    assert g.ctx.try_apply_bucket(0, v0, 1) == binding.EDUP
+    assert g.ctx.step() == (0, B - 1)
+    with pytest.raises(sh.ShadowError) as e:
+        g.ctx.snapshot(None, None, None)
+    assert e.value.status == binding.EBUSY
+    with pytest.raises(sh.ShadowError) as e:
+        g.ctx.set_lr(1e-4)
+    assert e.value.status == binding.EBUSY
+    assert g.ctx.try_apply_bucket(1, g._views[1], 2) == binding.ESTEP      # next iteration before this one is complete
+    for b in range(1, B):
+        assert g.ctx.try_apply_bucket(b, g._views[b], 1) == binding.OK
+    g.ctx.sync()
+    assert g.ctx.step() == (1, 0)
+    assert g.ctx.try_apply_bucket(0, v0, 1) == binding.ESTEP                # replay of a finished iteration
+    # the finished iteration equals the oracle's
+    inp = Inputs(wl)
+    orc = run_oracle_full(wl, inp, 1)
+    for b in range(B):
+        assert_state_matches(g.bucket_state(b), (orc.p[b], orc.m[b], orc.v[b]), f"errors bucket {b}")
+    g.close()
+
+
+def test_per_step_learning_rate():
+    """Cosine-annealed learning rate (section 6) supplied per iteration by the caller."""
+    say("case lr schedule")
+    import math
+    wl = custom("lr", RAGGED[:7], 2, "bf16", clip=0.0, cap=150_000, steps=5)
+    inp = Inputs(wl)
+    lrs = [float(np.float32(1e-3 * 0.5 * (1 + math.cos(math.pi * t / 5)))) for t in range(5)]
+    g = GpuShadow(wl, inp)
+    lay = oracle_layout(wl)
+    starts = lay.logical_starts()
+    orc = oracle.OracleShadow(lay, oracle.HParams(lr=lrs[0], weight_decay=wl.weight_decay),
+                              [inp.param_np(s, b.numel) for s, b in zip(starts, lay.buckets)])
+    for t in range(1, 6):
+        g.ctx.set_lr(lrs[t - 1])
+        orc.hp.lr = lrs[t - 1]
+        g.run_step(t)
+        orc.step({b: [inp.grad_np(t, w, starts[b], lay.buckets[b].numel) for w in range(2)] for b in range(len(lay.buckets))})
+    for b in range(len(lay.buckets)):
+        assert_state_matches(g.bucket_state(b), (orc.p[b], orc.m[b], orc.v[b]), f"lr bucket {b}")
+    g.close()

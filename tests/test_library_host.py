@@ -1,0 +1,108 @@
+"""Host-side checks of libshadow.so that need no GPU: exports, layout, argument validation."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2507_13522_amd as sh
+from paper_2507_13522_amd import binding
+import synth
+from harness import assert_layouts_agree, lib_layout, oracle_layout
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "shadow.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(shadow_[a-z_0-9]+)\s*\(", hdr))
+    assert len(declared) >= 20
+    L = sh.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), f"{name} declared in shadow.h but not exported"
+    assert declared == set(binding.EXPORTS)
+
+
+def test_strerror():
+    assert sh.shadow_strerror(0) == "ok"
+    for code in range(-7, 0):
+        assert sh.shadow_strerror(code) not in ("ok", "unknown status")
+    assert sh.shadow_strerror(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("name", list(synth.WORKLOADS))
+def test_layout_matches_oracle_on_workloads(name):
+    wl = synth.get_workload(name)
+    ol, ll = oracle_layout(wl), lib_layout(wl)
+    assert_layouts_agree(ol, ll)
+    if name == "tiny":
+        assert ll.num_buckets == 4
+    if name == "llama7b":
+        # 50 MiB of bf16 = 26,214,400 elements: embeddings, w1/w2/w3 exceed it and sit alone
+        sizes = [ll.bucket(b)[1] for b in range(ll.num_buckets)]
+        assert sizes.count(131_072_000) == 2 and sizes.count(45_088_768) == 96
+        assert max(s for s in sizes if s not in (131_072_000, 45_088_768)) <= 26_214_400
+
+
+def test_layout_matches_oracle_on_random_lists():
+    rng = np.random.default_rng(3)
+    for trial in range(30):
+        T = int(rng.integers(1, 60))
+        tensors = [(int(rng.integers(1, 3000)), bool(rng.integers(0, 2))) for _ in range(T)]
+        gb = int(rng.choice([2, 4]))
+        cap = int(rng.integers(100, 6000))
+        assert_layouts_agree(oracle.build_layout(tensors, gb, cap), sh.Layout(tensors, gb, cap))
+    tensors = [(7, True), (9, False), (11, True), (13, True)]
+    fixed = [1, 0, 1, 2]
+    assert_layouts_agree(oracle.build_layout(tensors, 4, 0, fixed), sh.Layout(tensors, 4, 0, fixed))
+
+
+def test_layout_rejects_bad_arguments():
+    with pytest.raises(sh.ShadowError):
+        sh.Layout([], 2, 100)
+    with pytest.raises(sh.ShadowError):
+        sh.Layout([(0, True)], 2, 100)
+    with pytest.raises(sh.ShadowError):
+        sh.Layout([(5, True)], 3, 100)
+    with pytest.raises(sh.ShadowError):
+        sh.Layout([(5, True)], 2, 0)
+    with pytest.raises(sh.ShadowError):
+        sh.Layout([(5, True), (6, True)], 2, 0, [0, 2])      # ids not dense
+    lay = sh.Layout([(5, True)], 2, 100)
+    with pytest.raises(sh.ShadowError) as e:
+        lay.bucket(1)
+    assert e.value.status == binding.EBUCKET
+
+
+def test_init_validates_before_touching_the_gpu():
+    lay = sh.Layout([(100, True)], 2, 1000)
+    good = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, max_grad_norm=0.0, num_workers=2,
+                grad_dtype=sh.GRAD_BF16, reduce_op=sh.REDUCE_MEAN, num_streams=1)
+    bad = [dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0), dict(lr=-1.0), dict(num_workers=0), dict(num_workers=65),
+           dict(grad_dtype=7), dict(grad_dtype=sh.GRAD_F32), dict(reduce_op=3), dict(num_streams=0), dict(num_streams=17),
+           dict(weight_decay=-1.0), dict(max_grad_norm=1.0)]          # clipping on but no scratch arena
+    for kw in bad:
+        hp = sh.HParams(**{**good, **kw})
+        with pytest.raises(sh.ShadowError) as e:
+            sh.Shadow(lay, hp, 256, 512, 768, None)
+        assert e.value.status == binding.EINVAL, kw
+    hp = sh.HParams(**good)
+    for ptrs in [(0, 512, 768), (256, 512 + 4, 768), (256, 256, 768)]:
+        with pytest.raises(sh.ShadowError) as e:
+            sh.Shadow(lay, hp, *ptrs, None)
+        assert e.value.status == binding.EINVAL
+    with pytest.raises(sh.ShadowError):       # scratch given although clipping is off
+        sh.Shadow(lay, hp, 256, 512, 768, 1024)
+
+
+def test_null_handles_are_rejected():
+    L = sh.lib()
+    assert L.shadow_sync(None) == binding.EINVAL
+    assert L.shadow_apply_bucket(None, 0, None, 1) == binding.EINVAL
+    assert L.shadow_snapshot(None, None, None, None, None) == binding.EINVAL
+    assert L.shadow_destroy(None) == binding.OK
+    assert L.shadow_set_tunable(b"nope", 1) == binding.EINVAL
+    assert L.shadow_copy_probe(None, None, 16, None) == binding.EINVAL
