@@ -190,10 +190,10 @@ int32_t shadow_copy_probe(void* d_dst, const void* d_src, uint64_t bytes, void* 
 
 const char* shadow_strerror(int32_t status);
 const char* shadow_last_hip_error(void);
-/* Tuning knobs of the launch shapes (for measurement sweeps): "fold_grid_cap"
- * (most blocks of a per-bucket kernel) and "adamw_grid_cap" (most blocks of the
- * whole-arena sweep); larger inputs are covered by grid-stride loops.  Applies
- * to contexts created later. */
+/* Tuning knobs of the launch shapes (for measurement sweeps): "fold_block"
+ * (threads per block of the per-bucket kernels) and "adamw_block" (of the
+ * whole-arena sweep); value in {64, 128, 256, 512, 1024}.  Applies to contexts
+ * created later. */
 int32_t shadow_set_tunable(const char* name, int64_t value);
 
 #ifdef __cplusplus

@@ -20,9 +20,11 @@ namespace {
 thread_local std::string g_hip_error;
 
 struct Tunables {
-    int64_t fold_grid_cap = 8192;     // blocks per bucket kernel (grid-stride beyond)
-    int64_t adamw_grid_cap = 16384;   // blocks of the whole-arena AdamW sweep
+    int64_t fold_block = 256;     // threads per block of the per-bucket kernels
+    int64_t adamw_block = 256;    // threads per block of the whole-arena AdamW sweep
 } g_tune;
+
+constexpr uint64_t kMaxThreadsPerLaunch = 1ull << 31;
 
 #define HIP_TRY(expr)                                                                         \
     do {                                                                                      \
@@ -73,6 +75,9 @@ struct shadow_ctx {
     uint8_t* d_run_flag = nullptr;
     uint32_t num_runs = 0;
     double* d_partial = nullptr;
+    double* d_stage1 = nullptr;
+    uint32_t nstage1 = 0;
+    uint32_t fold_block = 256, adamw_block = 256;
     float* d_coef = nullptr;
     double* d_sumsq = nullptr;
     std::vector<uint32_t> slot_base, slot_count;
@@ -166,12 +171,13 @@ void compute_scalars(const shadow_hparams& hp, uint64_t t, StepScalars& s)
     s.mean = hp.reduce_op == SHADOW_REDUCE_MEAN ? 1u : 0u;
 }
 
-uint32_t grid_for(uint64_t nvec, int64_t cap)
+// threads needed by a per-bucket kernel: one per 4 elements plus one for a ragged tail
+uint64_t bucket_threads(uint64_t numel) { return (numel >> 2) + ((numel & 3) ? 1 : 0); }
+
+uint32_t blocks_for(uint64_t threads, uint32_t block)
 {
-    uint64_t blocks = (nvec + kBlock - 1) / kBlock;
-    if (blocks < 1) blocks = 1;
-    if (int64_t(blocks) > cap) blocks = uint64_t(cap);
-    return uint32_t(blocks);
+    uint64_t blocks = (threads + block - 1) / block;
+    return uint32_t(blocks ? blocks : 1);
 }
 
 int32_t get_event(shadow_ctx* c, hipEvent_t* out)
@@ -202,15 +208,16 @@ struct ProfScope {
 template <bool BF16, int W>
 void launch_fold_adamw(shadow_ctx* c, const GradViews& gv, const BucketL& b, hipStream_t st, const WdMap& map)
 {
-    const uint32_t grid = grid_for(b.numel >> 3, g_tune.fold_grid_cap);
-    k_fold_adamw<BF16, W><<<grid, kBlock, 0, st>>>(gv, c->hp.num_workers, c->p + b.arena_off, c->m + b.arena_off,
+    const uint32_t grid = blocks_for(bucket_threads(b.numel), c->fold_block);
+    k_fold_adamw<BF16, W><<<grid, c->fold_block, 0, st>>>(gv, c->hp.num_workers, c->p + b.arena_off, c->m + b.arena_off,
                                                    c->v + b.arena_off, b.numel, b.arena_off, map, c->sc);
 }
 
 template <bool BF16, int W>
 void launch_fold_sumsq(shadow_ctx* c, const GradViews& gv, const BucketL& b, uint32_t bucket, hipStream_t st)
 {
-    k_fold_sumsq<BF16, W><<<c->slot_count[bucket], kBlock, 0, st>>>(gv, c->hp.num_workers, c->r + b.arena_off, b.numel,
+    const uint32_t grid = blocks_for(bucket_threads(b.numel), c->fold_block);
+    k_fold_sumsq<BF16, W><<<grid, c->fold_block, 0, st>>>(gv, c->hp.num_workers, c->r + b.arena_off, b.numel,
                                                                     c->d_partial + c->slot_base[bucket], c->sc);
 }
 
@@ -269,6 +276,7 @@ void free_ctx(shadow_ctx* c)
     (void)hipFree(c->d_run_start);
     (void)hipFree(c->d_run_flag);
     (void)hipFree(c->d_partial);
+    (void)hipFree(c->d_stage1);
     (void)hipFree(c->d_coef);
     (void)hipFree(c->d_sumsq);
     delete c;
@@ -325,12 +333,16 @@ int32_t build_tables(shadow_ctx* c)
         uint64_t total = 0;
         for (size_t b = 0; b < L.buckets.size(); ++b) {
             c->slot_base[b] = uint32_t(total);
-            c->slot_count[b] = grid_for(L.buckets[b].numel >> 3, g_tune.fold_grid_cap);
+            // one slot per wave of the bucket's fold launch
+            c->slot_count[b] = blocks_for(bucket_threads(L.buckets[b].numel), c->fold_block) * (c->fold_block / 64);
             total += c->slot_count[b];
             if (total > 0x7FFFFFFFull) return SHADOW_EINVAL;
         }
         c->nslots = uint32_t(total);
+        c->nstage1 = uint32_t((total + kNormChunk - 1) / kNormChunk);
+        if (c->nstage1 == 0) c->nstage1 = 1;
         HIP_TRY(hipMalloc(&c->d_partial, (total ? total : 1) * sizeof(double)));
+        HIP_TRY(hipMalloc(&c->d_stage1, c->nstage1 * sizeof(double)));
         HIP_TRY(hipMalloc(&c->d_coef, sizeof(float)));
         HIP_TRY(hipMalloc(&c->d_sumsq, sizeof(double)));
         HIP_TRY(hipMemset(c->d_partial, 0, (total ? total : 1) * sizeof(double)));
@@ -444,6 +456,9 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
     if (!aligned(d_param, 256) || !aligned(d_m, 256) || !aligned(d_v, 256) || !aligned(d_reduced, 256)) return SHADOW_EINVAL;
     if (d_param == d_m || d_param == d_v || d_m == d_v) return SHADOW_EINVAL;
 
+    for (const BucketL& b : layout->buckets)
+        if (bucket_threads(b.numel) > kMaxThreadsPerLaunch) return SHADOW_EINVAL;   // one launch per bucket
+
     shadow_ctx* c = new (std::nothrow) shadow_ctx();
     if (!c) return SHADOW_ENOMEM;
     int32_t rc = SHADOW_OK;
@@ -453,6 +468,8 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
         c->p = d_param; c->m = d_m; c->v = d_v; c->r = d_reduced;
         c->clip = clip;
         c->completed = start_step;
+        c->fold_block = uint32_t(g_tune.fold_block);
+        c->adamw_block = uint32_t(g_tune.adamw_block);
         c->arrived.assign(layout->buckets.size(), 0);
         c->stream_dirty.assign(hp->num_streams, 0);
         c->streams.assign(hp->num_streams, nullptr);
@@ -543,15 +560,21 @@ int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const
             {
                 ProfScope ps(c, SHADOW_K_NORM, s0);
                 if (ps.rc != SHADOW_OK) { c->poisoned = true; return ps.rc; }
-                k_norm_finalize<<<1, 1024, 0, s0>>>(c->d_partial, c->nslots, c->hp.max_grad_norm, c->d_coef, c->d_sumsq);
+                k_norm_stage1<<<c->nstage1, kNormBlock, 0, s0>>>(c->d_partial, c->nslots, c->d_stage1);
+                k_norm_finalize<<<1, kNormBlock, 0, s0>>>(c->d_stage1, c->nstage1, c->hp.max_grad_norm, c->d_coef, c->d_sumsq);
                 if ((e = hipGetLastError()) != hipSuccess) return hip_fail("norm kernel launch", e);
                 if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
             }
             {
                 ProfScope ps(c, SHADOW_K_ADAMW, s0);
                 if (ps.rc != SHADOW_OK) { c->poisoned = true; return ps.rc; }
-                const uint64_t nvec = c->lay.arena_numel >> 3;
-                k_adamw<<<grid_for(nvec, g_tune.adamw_grid_cap), kBlock, 0, s0>>>(c->r, c->p, c->m, c->v, nvec, c->d_coef, map, c->sc);
+                const uint64_t nvec = c->lay.arena_numel >> 2;      // the arena is a multiple of 64 elements
+                const uint64_t per_launch = kMaxThreadsPerLaunch / c->adamw_block;
+                const uint64_t blocks = (nvec + c->adamw_block - 1) / c->adamw_block;
+                for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
+                    const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
+                    k_adamw<<<uint32_t(nb), c->adamw_block, 0, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc);
+                }
                 if ((e = hipGetLastError()) != hipSuccess) return hip_fail("adamw kernel launch", e);
                 if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
             }
@@ -667,8 +690,14 @@ int32_t shadow_copy_probe(void* d_dst, const void* d_src, uint64_t bytes, void* 
     if (!d_dst || !d_src || (bytes & 15) || !aligned(d_dst, 16) || !aligned(d_src, 16)) return SHADOW_EINVAL;
     const uint64_t n16 = bytes >> 4;
     if (n16 == 0) return SHADOW_OK;
-    k_copy<<<grid_for(n16, g_tune.adamw_grid_cap), kBlock, 0, static_cast<hipStream_t>(stream)>>>(
-        static_cast<const u32x4*>(d_src), static_cast<u32x4*>(d_dst), n16);
+    const uint32_t block = 256;
+    const uint64_t per_launch = kMaxThreadsPerLaunch / block;
+    const uint64_t blocks = (n16 + block - 1) / block;
+    for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
+        const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
+        k_copy<<<uint32_t(nb), block, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const u32x4*>(d_src),
+                                                                             static_cast<u32x4*>(d_dst), n16, b0);
+    }
     HIP_TRY(hipGetLastError());
     return SHADOW_OK;
 }
@@ -692,9 +721,10 @@ const char* shadow_last_hip_error(void) { return g_hip_error.c_str(); }
 
 int32_t shadow_set_tunable(const char* name, int64_t value)
 {
-    if (!name || value < 1 || value > (1 << 30)) return SHADOW_EINVAL;
-    if (!std::strcmp(name, "fold_grid_cap")) g_tune.fold_grid_cap = value;
-    else if (!std::strcmp(name, "adamw_grid_cap")) g_tune.adamw_grid_cap = value;
+    if (!name) return SHADOW_EINVAL;
+    if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return SHADOW_EINVAL;
+    if (!std::strcmp(name, "fold_block")) g_tune.fold_block = value;
+    else if (!std::strcmp(name, "adamw_block")) g_tune.adamw_block = value;
     else return SHADOW_EINVAL;
     return SHADOW_OK;
 }

@@ -20,12 +20,13 @@
 // compiled with -ffp-contract=off and correctly rounded divide/sqrt, denormals
 // kept), so results do not depend on launch shape, bucket order or stream.
 //
-// Memory plan: each lane owns 8 consecutive elements per trip: one 128-bit load
-// per bfloat16 view (two per float view), two 128-bit loads and stores for each
-// of p, m, v.  A wave therefore touches 1 KiB (bf16) / 2 KiB (fp32) contiguous
-// per stream per instruction, and all W loads of a trip are issued before the
-// first add so that W+3 independent requests per lane are in flight.  Gradient
-// and reduced-gradient reads are single-use and marked non-temporal.
+// Memory plan (from measurement on MI355X): one lane owns 4 consecutive
+// elements and makes exactly one trip: one 64-bit load per bfloat16 view (one
+// 128-bit load per float view) and one 128-bit load and store for each of p, m,
+// v.  Grids are flat (one block per 4*blockDim elements, no grid-stride loop)
+// so the hardware keeps refilling CUs with fresh waves whose loads are all
+// issued before the first use; every global access carries the non-temporal
+// hint, since no line is touched twice within a kernel.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -34,9 +35,10 @@ namespace shadow {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kBlock = 256;          // 4 waves
-constexpr int kVec = 8;              // elements per lane per trip
+constexpr int kVec = 4;              // elements per lane
+constexpr int kMaxBlock = 1024;
 constexpr int kMaxWorkers = 64;
 constexpr int kWdTileShift = 10;     // weight-decay map granularity: 1024 elements
 
@@ -60,19 +62,10 @@ struct WdMap {
     uint32_t num_runs;
 };
 
-#ifndef SHADOW_NT_LOADS
-#define SHADOW_NT_LOADS 1
-#endif
-
 template <typename T>
-__device__ __forceinline__ T load_once(const T* p)
-{
-#if SHADOW_NT_LOADS
-    return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
-}
+__device__ __forceinline__ T load_once(const T* p) { return __builtin_nontemporal_load(p); }
+template <typename T>
+__device__ __forceinline__ void store_once(T* p, T v) { __builtin_nontemporal_store(v, p); }
 
 __device__ __forceinline__ float bits_to_float(uint32_t b) { return __builtin_bit_cast(float, b); }
 
@@ -97,99 +90,64 @@ __device__ __forceinline__ void adamw_elem(float& p, float& m, float& v, float g
     p = p - s.step_size * (m / denom);
 }
 
-// ---- fold of 8 consecutive elements --------------------------------------------------
-// W > 0: compile-time worker count, loads issued in batches of up to kBatch views before the
-// adds (which stay strictly in worker order); W == 0: run-time worker count.
-__device__ __forceinline__ void widen_first(const u32x4& a, float (&r)[kVec])
+// ---- fold of 4 consecutive elements ---------------------------------------------------
+// W > 0: compile-time worker count, all loads of a batch issued before the adds (which stay
+// strictly in worker order); W == 0: run-time worker count.
+__device__ __forceinline__ void widen_first(const u32x2& a, f32x4& r)
 {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        r[2 * k] = bits_to_float(a[k] << 16);          // even element: low half-word
-        r[2 * k + 1] = bits_to_float(a[k] & 0xFFFF0000u);
-    }
+    r[0] = bits_to_float(a[0] << 16);              // even element: low half-word
+    r[1] = bits_to_float(a[0] & 0xFFFF0000u);
+    r[2] = bits_to_float(a[1] << 16);
+    r[3] = bits_to_float(a[1] & 0xFFFF0000u);
 }
 
-__device__ __forceinline__ void widen_add(const u32x4& a, float (&r)[kVec])
+__device__ __forceinline__ void widen_add(const u32x2& a, f32x4& r)
 {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        r[2 * k] = r[2 * k] + bits_to_float(a[k] << 16);
-        r[2 * k + 1] = r[2 * k + 1] + bits_to_float(a[k] & 0xFFFF0000u);
-    }
-}
-
-template <int W>
-__device__ __forceinline__ void fold8_bf16(const GradViews& gv, uint32_t w_rt, uint64_t vec, float (&r)[kVec])
-{
-    if constexpr (W > 0) {
-        constexpr int kBatch = 16;
-#pragma unroll
-        for (int w0 = 0; w0 < W; w0 += kBatch) {
-            u32x4 raw[kBatch];
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j)
-                if (w0 + j < W) raw[j] = load_once(reinterpret_cast<const u32x4*>(gv.ptr[w0 + j]) + vec);
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j) {
-                if (w0 + j < W) {
-                    if (w0 + j == 0) widen_first(raw[j], r); else widen_add(raw[j], r);
-                }
-            }
-        }
-    } else {
-        widen_first(load_once(reinterpret_cast<const u32x4*>(gv.ptr[0]) + vec), r);
-        for (uint32_t w = 1; w < w_rt; ++w) widen_add(load_once(reinterpret_cast<const u32x4*>(gv.ptr[w]) + vec), r);
-    }
-}
-
-template <int W>
-__device__ __forceinline__ void fold8_f32(const GradViews& gv, uint32_t w_rt, uint64_t vec, float (&r)[kVec])
-{
-    if constexpr (W > 0) {
-        constexpr int kBatch = 8;
-#pragma unroll
-        for (int w0 = 0; w0 < W; w0 += kBatch) {
-            f32x4 lo[kBatch], hi[kBatch];
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j) {
-                if (w0 + j < W) {
-                    lo[j] = load_once(reinterpret_cast<const f32x4*>(gv.ptr[w0 + j]) + 2 * vec);
-                    hi[j] = load_once(reinterpret_cast<const f32x4*>(gv.ptr[w0 + j]) + 2 * vec + 1);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j) {
-                if (w0 + j < W) {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        if (w0 + j == 0) { r[k] = lo[j][k]; r[4 + k] = hi[j][k]; }
-                        else { r[k] = r[k] + lo[j][k]; r[4 + k] = r[4 + k] + hi[j][k]; }
-                    }
-                }
-            }
-        }
-    } else {
-        f32x4 a = load_once(reinterpret_cast<const f32x4*>(gv.ptr[0]) + 2 * vec);
-        f32x4 b = load_once(reinterpret_cast<const f32x4*>(gv.ptr[0]) + 2 * vec + 1);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) { r[k] = a[k]; r[4 + k] = b[k]; }
-        for (uint32_t w = 1; w < w_rt; ++w) {
-            a = load_once(reinterpret_cast<const f32x4*>(gv.ptr[w]) + 2 * vec);
-            b = load_once(reinterpret_cast<const f32x4*>(gv.ptr[w]) + 2 * vec + 1);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) { r[k] = r[k] + a[k]; r[4 + k] = r[4 + k] + b[k]; }
-        }
-    }
+    r[0] = r[0] + bits_to_float(a[0] << 16);
+    r[1] = r[1] + bits_to_float(a[0] & 0xFFFF0000u);
+    r[2] = r[2] + bits_to_float(a[1] << 16);
+    r[3] = r[3] + bits_to_float(a[1] & 0xFFFF0000u);
 }
 
 template <bool BF16, int W>
-__device__ __forceinline__ void fold8(const GradViews& gv, uint32_t w_rt, uint64_t vec, float (&r)[kVec], const StepScalars& s)
+__device__ __forceinline__ f32x4 fold4(const GradViews& gv, uint32_t w_rt, uint64_t vec, const StepScalars& s)
 {
-    if constexpr (BF16) fold8_bf16<W>(gv, w_rt, vec, r); else fold8_f32<W>(gv, w_rt, vec, r);
-    if (s.mean) {
+    f32x4 r;
+    if constexpr (BF16) {
+        if constexpr (W > 0) {
+            u32x2 raw[W];
 #pragma unroll
-        for (int k = 0; k < kVec; ++k) r[k] = r[k] * s.inv_w;
+            for (int w = 0; w < W; ++w) raw[w] = load_once(reinterpret_cast<const u32x2*>(gv.ptr[w]) + vec);
+            widen_first(raw[0], r);
+#pragma unroll
+            for (int w = 1; w < W; ++w) widen_add(raw[w], r);
+        } else {
+            widen_first(load_once(reinterpret_cast<const u32x2*>(gv.ptr[0]) + vec), r);
+            for (uint32_t w = 1; w < w_rt; ++w) widen_add(load_once(reinterpret_cast<const u32x2*>(gv.ptr[w]) + vec), r);
+        }
+    } else {
+        if constexpr (W > 0) {
+            constexpr int kBatch = 16;
+#pragma unroll
+            for (int w0 = 0; w0 < W; w0 += kBatch) {
+                f32x4 raw[kBatch];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j)
+                    if (w0 + j < W) raw[j] = load_once(reinterpret_cast<const f32x4*>(gv.ptr[w0 + j]) + vec);
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    if (w0 + j < W) {
+                        if (w0 + j == 0) r = raw[j]; else r = r + raw[j];
+                    }
+                }
+            }
+        } else {
+            r = load_once(reinterpret_cast<const f32x4*>(gv.ptr[0]) + vec);
+            for (uint32_t w = 1; w < w_rt; ++w) r = r + load_once(reinterpret_cast<const f32x4*>(gv.ptr[w]) + vec);
+        }
     }
+    if (s.mean) r = r * s.inv_w;
+    return r;
 }
 
 // one element (ragged tail of a bucket)
@@ -209,75 +167,79 @@ __device__ __forceinline__ float fold1(const GradViews& gv, uint32_t w_rt, uint6
     return acc;
 }
 
-__device__ __forceinline__ void load8(const float* base, uint64_t vec, float (&x)[kVec])
-{
-    f32x4 a = reinterpret_cast<const f32x4*>(base)[2 * vec];
-    f32x4 b = reinterpret_cast<const f32x4*>(base)[2 * vec + 1];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) { x[k] = a[k]; x[4 + k] = b[k]; }
-}
-
-__device__ __forceinline__ void load8_once(const float* base, uint64_t vec, float (&x)[kVec])
-{
-    f32x4 a = load_once(reinterpret_cast<const f32x4*>(base) + 2 * vec);
-    f32x4 b = load_once(reinterpret_cast<const f32x4*>(base) + 2 * vec + 1);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) { x[k] = a[k]; x[4 + k] = b[k]; }
-}
-
-__device__ __forceinline__ void store8(float* base, uint64_t vec, const float (&x)[kVec])
-{
-    f32x4 a, b;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) { a[k] = x[k]; b[k] = x[4 + k]; }
-    reinterpret_cast<f32x4*>(base)[2 * vec] = a;
-    reinterpret_cast<f32x4*>(base)[2 * vec + 1] = b;
-}
-
-// AdamW on 8 consecutive arena elements starting at arena element e0 (multiple of 8).
-__device__ __forceinline__ void adamw8(float* p, float* m, float* v, uint64_t vec, uint64_t e0, const float (&g)[kVec],
+// AdamW on 4 consecutive arena elements starting at arena element e0 (multiple of 4).
+__device__ __forceinline__ void adamw4(float* p, float* m, float* v, uint64_t vec, uint64_t e0, const f32x4& g,
                                        const WdMap& map, const StepScalars& s)
 {
-    float pp[kVec], mm[kVec], vv[kVec];
-    load8(p, vec, pp);
-    load8(m, vec, mm);
-    load8(v, vec, vv);
+    f32x4 pp = load_once(reinterpret_cast<const f32x4*>(p) + vec);
+    f32x4 mm = load_once(reinterpret_cast<const f32x4*>(m) + vec);
+    f32x4 vv = load_once(reinterpret_cast<const f32x4*>(v) + vec);
     const uint8_t mode = map.tile_mode[e0 >> kWdTileShift];
-    if (mode != 2) {
-        const float dfac = mode ? s.decay : 1.0f;
+    const float uniform = mode ? s.decay : 1.0f;
 #pragma unroll
-        for (int k = 0; k < kVec; ++k) adamw_elem(pp[k], mm[k], vv[k], g[k], dfac, s);
-    } else {
-#pragma unroll
-        for (int k = 0; k < kVec; ++k) adamw_elem(pp[k], mm[k], vv[k], g[k], decay_factor_of(map, e0 + k, s.decay), s);
+    for (int k = 0; k < kVec; ++k) {
+        const float dfac = (mode != 2) ? uniform : decay_factor_of(map, e0 + k, s.decay);
+        float pk = pp[k], mk = mm[k], vk = vv[k];
+        adamw_elem(pk, mk, vk, g[k], dfac, s);
+        pp[k] = pk; mm[k] = mk; vv[k] = vk;
     }
-    store8(p, vec, pp);
-    store8(m, vec, mm);
-    store8(v, vec, vv);
+    store_once(reinterpret_cast<f32x4*>(p) + vec, pp);
+    store_once(reinterpret_cast<f32x4*>(m) + vec, mm);
+    store_once(reinterpret_cast<f32x4*>(v) + vec, vv);
 }
 
 // ---- kernel: fold + AdamW in one pass (clipping off) ---------------------------------
 // p, m, v point at the bucket's first element; arena_off is that element's arena index.
+// Thread i < n/4 owns elements 4i..4i+3; thread n/4 owns the (n mod 4) tail elements.
 template <bool BF16, int W>
-__global__ __launch_bounds__(kBlock) void k_fold_adamw(GradViews gv, uint32_t w_rt, float* __restrict__ p,
-                                                       float* __restrict__ m, float* __restrict__ v, uint64_t n,
-                                                       uint64_t arena_off, WdMap map, StepScalars s)
+__global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(GradViews gv, uint32_t w_rt, float* __restrict__ p,
+                                                          float* __restrict__ m, float* __restrict__ v, uint64_t n,
+                                                          uint64_t arena_off, WdMap map, StepScalars s)
 {
-    const uint64_t nvec = n >> 3;
-    const uint64_t stride = uint64_t(gridDim.x) * kBlock;
-    for (uint64_t vec = uint64_t(blockIdx.x) * kBlock + threadIdx.x; vec < nvec; vec += stride) {
-        float r[kVec];
-        fold8<BF16, W>(gv, w_rt, vec, r, s);
-        adamw8(p, m, v, vec, arena_off + (vec << 3), r, map, s);
+    const uint64_t nvec = n >> 2;
+    const uint64_t vec = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (vec < nvec) {
+        const f32x4 r = fold4<BF16, W>(gv, w_rt, vec, s);
+        adamw4(p, m, v, vec, arena_off + (vec << 2), r, map, s);
+    } else if (vec == nvec) {
+        for (uint64_t e = nvec << 2; e < n; ++e) {
+            float g = fold1<BF16>(gv, w_rt, e, s);
+            float pp = p[e], mm = m[e], vv = v[e];
+            adamw_elem(pp, mm, vv, g, decay_factor_of(map, arena_off + e, s.decay), s);
+            p[e] = pp; m[e] = mm; v[e] = vv;
+        }
     }
-    const uint32_t tail = uint32_t(n & 7);
-    if (blockIdx.x == 0 && threadIdx.x < tail) {
-        const uint64_t e = (nvec << 3) + threadIdx.x;
-        float g = fold1<BF16>(gv, w_rt, e, s);
-        float pp = p[e], mm = m[e], vv = v[e];
-        adamw_elem(pp, mm, vv, g, decay_factor_of(map, arena_off + e, s.decay), s);
-        p[e] = pp; m[e] = mm; v[e] = vv;
+}
+
+// ---- kernel: fold + sum of squares, reduced gradient stored (clipping on) -------------
+// r_out points at the bucket's first scratch element.  Every wave writes the sum of its
+// lanes' squares to its own slot, partial[global wave index]: no barrier, fixed order.
+template <bool BF16, int W>
+__global__ __launch_bounds__(kMaxBlock) void k_fold_sumsq(GradViews gv, uint32_t w_rt, float* __restrict__ r_out, uint64_t n,
+                                                          double* __restrict__ partial, StepScalars s)
+{
+    const uint64_t nvec = n >> 2;
+    const uint64_t vec = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    double acc = 0.0;
+    if (vec < nvec) {
+        const f32x4 r = fold4<BF16, W>(gv, w_rt, vec, s);
+        store_once(reinterpret_cast<f32x4*>(r_out) + vec, r);
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) {
+            const double d = double(r[k]);
+            acc = fma(d, d, acc);        // d*d is exact in double, so this equals acc + d*d
+        }
+    } else if (vec == nvec) {
+        for (uint64_t e = nvec << 2; e < n; ++e) {
+            const float g = fold1<BF16>(gv, w_rt, e, s);
+            r_out[e] = g;
+            const double d = double(g);
+            acc = fma(d, d, acc);
+        }
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if ((threadIdx.x & 63) == 0) partial[vec >> 6] = acc;
 }
 
 // ---- block-wide sum of doubles in a fixed order ----------------------------------------
@@ -296,45 +258,28 @@ __device__ __forceinline__ double block_sum(double x, double* lds)
     return t;   // valid in thread 0
 }
 
-// ---- kernel: fold + sum of squares, reduced gradient stored (clipping on) -------------
-// r_out points at the bucket's first scratch element; partial has gridDim.x slots.
-template <bool BF16, int W>
-__global__ __launch_bounds__(kBlock) void k_fold_sumsq(GradViews gv, uint32_t w_rt, float* __restrict__ r_out, uint64_t n,
-                                                       double* __restrict__ partial, StepScalars s)
+// ---- kernels: norm and clip coefficient, two stages with fixed summation order ---------
+// stage 1: block b sums slots [b*chunk, (b+1)*chunk), lane t taking every blockDim-th slot
+constexpr int kNormBlock = 1024;
+constexpr uint32_t kNormChunk = kNormBlock * 16;
+__global__ __launch_bounds__(kNormBlock) void k_norm_stage1(const double* __restrict__ partial, uint32_t nslots,
+                                                            double* __restrict__ stage1)
 {
-    __shared__ double lds[kBlock / 64];
-    const uint64_t nvec = n >> 3;
-    const uint64_t stride = uint64_t(gridDim.x) * kBlock;
+    __shared__ double lds[kNormBlock / 64];
+    const uint64_t lo = uint64_t(blockIdx.x) * kNormChunk;
+    const uint64_t hi = (lo + kNormChunk < nslots) ? lo + kNormChunk : nslots;
     double acc = 0.0;
-    for (uint64_t vec = uint64_t(blockIdx.x) * kBlock + threadIdx.x; vec < nvec; vec += stride) {
-        float r[kVec];
-        fold8<BF16, W>(gv, w_rt, vec, r, s);
-        store8(r_out, vec, r);
-#pragma unroll
-        for (int k = 0; k < kVec; ++k) {
-            const double d = double(r[k]);
-            acc = fma(d, d, acc);        // d*d is exact in double, so this equals acc + d*d
-        }
-    }
-    const uint32_t tail = uint32_t(n & 7);
-    if (blockIdx.x == 0 && threadIdx.x < tail) {
-        const uint64_t e = (nvec << 3) + threadIdx.x;
-        const float g = fold1<BF16>(gv, w_rt, e, s);
-        r_out[e] = g;
-        const double d = double(g);
-        acc = fma(d, d, acc);
-    }
+    for (uint64_t i = lo + threadIdx.x; i < hi; i += kNormBlock) acc += load_once(partial + i);
     const double t = block_sum(acc, lds);
-    if (threadIdx.x == 0) partial[blockIdx.x] = t;
+    if (threadIdx.x == 0) stage1[blockIdx.x] = t;
 }
 
-// ---- kernel: norm and clip coefficient (one block, fixed summation order) --------------
-__global__ __launch_bounds__(1024) void k_norm_finalize(const double* __restrict__ partial, uint32_t nslots, float max_norm,
-                                                        float* __restrict__ coef_out, double* __restrict__ sumsq_out)
+__global__ __launch_bounds__(kNormBlock) void k_norm_finalize(const double* __restrict__ stage1, uint32_t n1, float max_norm,
+                                                              float* __restrict__ coef_out, double* __restrict__ sumsq_out)
 {
-    __shared__ double lds[1024 / 64];
+    __shared__ double lds[kNormBlock / 64];
     double acc = 0.0;
-    for (uint32_t i = threadIdx.x; i < nslots; i += blockDim.x) acc += partial[i];
+    for (uint32_t i = threadIdx.x; i < n1; i += kNormBlock) acc += stage1[i];
     const double S = block_sum(acc, lds);
     if (threadIdx.x == 0) {
         const double norm = sqrt(S);
@@ -346,26 +291,25 @@ __global__ __launch_bounds__(1024) void k_norm_finalize(const double* __restrict
 }
 
 // ---- kernel: AdamW over the whole arena from the stored reduced gradient ---------------
-__global__ __launch_bounds__(kBlock) void k_adamw(const float* __restrict__ r, float* __restrict__ p, float* __restrict__ m,
-                                                  float* __restrict__ v, uint64_t nvec, const float* __restrict__ coef,
-                                                  WdMap map, StepScalars s)
+// block_base lets one logical sweep be issued as several launches (grid size limit).
+__global__ __launch_bounds__(kMaxBlock) void k_adamw(const float* __restrict__ r, float* __restrict__ p, float* __restrict__ m,
+                                                     float* __restrict__ v, uint64_t nvec, uint64_t block_base,
+                                                     const float* __restrict__ coef, WdMap map, StepScalars s)
 {
+    const uint64_t vec = (block_base + blockIdx.x) * blockDim.x + threadIdx.x;
+    if (vec >= nvec) return;
     const float c = *coef;
-    const uint64_t stride = uint64_t(gridDim.x) * kBlock;
-    for (uint64_t vec = uint64_t(blockIdx.x) * kBlock + threadIdx.x; vec < nvec; vec += stride) {
-        float g[kVec];
-        load8_once(r, vec, g);
-#pragma unroll
-        for (int k = 0; k < kVec; ++k) g[k] = g[k] * c;
-        adamw8(p, m, v, vec, vec << 3, g, map, s);
-    }
+    f32x4 g = load_once(reinterpret_cast<const f32x4*>(r) + vec);
+    g = g * c;
+    adamw4(p, m, v, vec, vec << 2, g, map, s);
 }
 
 // ---- kernel: plain copy (bandwidth yardstick) ------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n16)
+__global__ __launch_bounds__(kMaxBlock) void k_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n16,
+                                                    uint64_t block_base)
 {
-    const uint64_t stride = uint64_t(gridDim.x) * kBlock;
-    for (uint64_t i = uint64_t(blockIdx.x) * kBlock + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+    const uint64_t i = (block_base + blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n16) store_once(dst + i, load_once(src + i));
 }
 
 }  // namespace shadow
