@@ -55,12 +55,29 @@ class Inputs:
             return synth.tiled(self._tile("param"), idx)
         return synth.param_values(self.wl.seed, idx, self.wl.param_sigma)
 
+    def _range_np(self, key, start: int, n: int) -> np.ndarray:
+        """Values at the contiguous logical range [start, start+n) of a tiled input (wrap-around copies)."""
+        tile = self._tile(key).numpy()
+        L = tile.size
+        out = np.empty(n, tile.dtype)
+        pos, src = 0, start % L
+        while pos < n:
+            k = min(L - src, n - pos)
+            out[pos:pos + k] = tile[src:src + k]
+            pos += k
+            src = 0
+        return out
+
     def grad_np(self, step: int, w: int, start: int, n: int) -> np.ndarray:
-        t = self.grad_at(step, w, torch.arange(start, start + n, dtype=torch.int64))
-        a = t.numpy()
+        if self.period:
+            a = self._range_np((step, w), start, n)
+        else:
+            a = self.grad_at(step, w, torch.arange(start, start + n, dtype=torch.int64)).numpy()
         return a.view(np.uint16).copy() if self.wl.grad_dtype == "bf16" else a.copy()
 
     def param_np(self, start: int, n: int) -> np.ndarray:
+        if self.period:
+            return self._range_np("param", start, n)
         return self.param_at(torch.arange(start, start + n, dtype=torch.int64)).numpy().copy()
 
     # -- GPU ---------------------------------------------------------------
