@@ -86,7 +86,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama7b")
-    ap.add_argument("--streams", type=int, default=2)
+    ap.add_argument("--streams", type=int, default=None)
+    ap.add_argument("--batch-mib", type=int, default=None,
+                    help="bucket scheduling: gradient MiB buffered per stream before one fold launch (0 = every bucket "
+                         "its own launch; default: the whole iteration in as few launches as the descriptor allows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fold-block", type=int, default=0)
     ap.add_argument("--adamw-block", type=int, default=0)
@@ -102,7 +105,9 @@ def main() -> int:
     import torch
     import paper_2507_13522_amd as sh
     import synth
-    from harness import GpuShadow, Inputs, TILE_PERIOD
+    from harness import BENCH_BATCH_BYTES, BENCH_STREAMS, GpuShadow, Inputs, TILE_PERIOD
+    streams = BENCH_STREAMS if args.streams is None else args.streams
+    batch_bytes = BENCH_BATCH_BYTES if args.batch_mib is None else args.batch_mib << 20
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -114,7 +119,7 @@ def main() -> int:
 
     wl = synth.get_workload(args.workload)
     inputs = Inputs(wl, period=TILE_PERIOD)
-    g = GpuShadow(wl, inputs, num_streams=args.streams)
+    g = GpuShadow(wl, inputs, num_streams=streams, batch_bytes=batch_bytes)
     P = g.layout.num_params
     g.fill_grads(1)            # the same resident views serve every timed step (values do not affect timing)
     step = 0
@@ -175,7 +180,8 @@ def main() -> int:
                                f"{wl.bucket_cap_bytes >> 20} MiB, W={wl.num_workers} {wl.grad_dtype} gradient views per bucket, "
                                f"AdamW" + (f" + global-norm clip at {wl.max_grad_norm}" if wl.max_grad_norm > 0 else ""),
                    "num_params": P, "num_buckets": len(g.buckets), "num_workers": wl.num_workers,
-                   "grad_dtype": wl.grad_dtype, "streams": args.streams},
+                   "grad_dtype": wl.grad_dtype, "streams": streams,
+                   "batch_bytes": batch_bytes},
         "hbm_GBps": total_gbs,
         "hbm_frac_of_peak": total_gbs / HBM_PEAK_GBS,
         "bytes_per_param": bpp["total"],

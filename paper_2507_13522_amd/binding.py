@@ -27,7 +27,8 @@ class TensorDesc(C.Structure):
 class HParams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float), ("max_grad_norm", C.c_float), ("num_workers", C.c_uint32),
-                ("grad_dtype", C.c_uint32), ("reduce_op", C.c_uint32), ("num_streams", C.c_uint32)]
+                ("grad_dtype", C.c_uint32), ("reduce_op", C.c_uint32), ("num_streams", C.c_uint32),
+                ("batch_bytes", C.c_uint64)]
 
 
 class ShadowError(RuntimeError):
@@ -49,6 +50,9 @@ _SIGS = {
     "shadow_layout_arena_numel": [C.c_void_p, C.POINTER(C.c_uint64)],
     "shadow_layout_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)],
     "shadow_layout_tensor": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)],
+    "shadow_layout_arena_stride": [C.c_void_p, C.POINTER(C.c_uint64)],
+    "shadow_layout_staging_bytes": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64)],
+    "shadow_layout_staging_view": [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64)],
     "shadow_init": [C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(HParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p)],
     "shadow_apply_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64],
     "shadow_snapshot": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64)],
@@ -140,6 +144,22 @@ class Layout:
         b, ob, oa = C.c_uint32(), C.c_uint64(), C.c_uint64()
         _check(lib().shadow_layout_tensor(self._h, t, C.byref(b), C.byref(ob), C.byref(oa)), "shadow_layout_tensor")
         return b.value, ob.value, oa.value
+
+    def arena_stride(self) -> int:
+        """Recommended byte distance between the arenas inside one device allocation."""
+        v = C.c_uint64()
+        _check(lib().shadow_layout_arena_stride(self._h, C.byref(v)), "shadow_layout_arena_stride")
+        return v.value
+
+    def staging_bytes(self, num_workers: int) -> int:
+        v = C.c_uint64()
+        _check(lib().shadow_layout_staging_bytes(self._h, num_workers, C.byref(v)), "shadow_layout_staging_bytes")
+        return v.value
+
+    def staging_view(self, num_workers: int, bucket: int, worker: int) -> int:
+        v = C.c_uint64()
+        _check(lib().shadow_layout_staging_view(self._h, num_workers, bucket, worker, C.byref(v)), "shadow_layout_staging_view")
+        return v.value
 
     def close(self) -> None:
         if getattr(self, "_h", None):

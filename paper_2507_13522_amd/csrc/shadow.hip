@@ -20,8 +20,10 @@ namespace {
 thread_local std::string g_hip_error;
 
 struct Tunables {
-    int64_t fold_block = 256;     // threads per block of the per-bucket kernels
-    int64_t adamw_block = 256;    // threads per block of the whole-arena AdamW sweep
+    int64_t fold_block = 1024;    // threads per block of the per-bucket kernels
+    int64_t adamw_block = 512;    // threads per block of the whole-arena AdamW sweep
+    int64_t fold_lds = 0;         // bytes of LDS reserved per block only to cap the waves resident per CU
+    int64_t adamw_lds = 65536;    // 2 blocks of 512 threads (16 waves) per CU
 } g_tune;
 
 constexpr uint64_t kMaxThreadsPerLaunch = 1ull << 31;
@@ -77,7 +79,7 @@ struct shadow_ctx {
     double* d_partial = nullptr;
     double* d_stage1 = nullptr;
     uint32_t nstage1 = 0;
-    uint32_t fold_block = 256, adamw_block = 256;
+    uint32_t fold_block = 1024, adamw_block = 512, fold_lds = 0, adamw_lds = 65536;
     float* d_coef = nullptr;
     double* d_sumsq = nullptr;
     std::vector<uint32_t> slot_base, slot_count;
@@ -93,6 +95,10 @@ struct shadow_ctx {
     bool boundary_pending = false;        // streams must wait on boundary_ev before new work
     std::vector<uint8_t> stream_dirty;    // stream has work since the last join
     bool poisoned = false;
+    // buckets accepted but not yet launched, per stream (see hp.batch_bytes)
+    struct Pending { uint32_t bucket; const void* ptr[kMaxWorkers]; };
+    std::vector<std::vector<Pending>> pending;
+    std::vector<uint64_t> pending_bytes;
     // profiling
     bool profile = false;
     struct Span { hipEvent_t a, b; };
@@ -206,41 +212,24 @@ struct ProfScope {
 };
 
 template <bool BF16, int W>
-void launch_fold_adamw(shadow_ctx* c, const GradViews& gv, const BucketL& b, hipStream_t st, const WdMap& map)
+void launch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map)
 {
-    const uint32_t grid = blocks_for(bucket_threads(b.numel), c->fold_block);
-    k_fold_adamw<BF16, W><<<grid, c->fold_block, 0, st>>>(gv, c->hp.num_workers, c->p + b.arena_off, c->m + b.arena_off,
-                                                   c->v + b.arena_off, b.numel, b.arena_off, map, c->sc);
-}
-
-template <bool BF16, int W>
-void launch_fold_sumsq(shadow_ctx* c, const GradViews& gv, const BucketL& b, uint32_t bucket, hipStream_t st)
-{
-    const uint32_t grid = blocks_for(bucket_threads(b.numel), c->fold_block);
-    k_fold_sumsq<BF16, W><<<grid, c->fold_block, 0, st>>>(gv, c->hp.num_workers, c->r + b.arena_off, b.numel,
-                                                                    c->d_partial + c->slot_base[bucket], c->sc);
+    if (c->clip) k_fold_sumsq<BF16, W><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->r, c->d_partial, c->sc);
+    else k_fold_adamw<BF16, W><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, map, c->sc);
 }
 
 template <bool BF16>
-void dispatch_fold(shadow_ctx* c, const GradViews& gv, const BucketL& b, uint32_t bucket, hipStream_t st, const WdMap& map)
+void dispatch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map)
 {
-#define SHADOW_CASE(WV)                                                                       \
-    case WV:                                                                                  \
-        if (c->clip) launch_fold_sumsq<BF16, WV>(c, gv, b, bucket, st);                       \
-        else launch_fold_adamw<BF16, WV>(c, gv, b, st, map);                                  \
-        break;
     switch (c->hp.num_workers) {
-        SHADOW_CASE(1)
-        SHADOW_CASE(2)
-        SHADOW_CASE(4)
-        SHADOW_CASE(8)
-        SHADOW_CASE(16)
-        SHADOW_CASE(32)
-        default:
-            if (c->clip) launch_fold_sumsq<BF16, 0>(c, gv, b, bucket, st);
-            else launch_fold_adamw<BF16, 0>(c, gv, b, st, map);
+        case 1: launch_fold<BF16, 1>(c, fb, grid, st, map); break;
+        case 2: launch_fold<BF16, 2>(c, fb, grid, st, map); break;
+        case 4: launch_fold<BF16, 4>(c, fb, grid, st, map); break;
+        case 8: launch_fold<BF16, 8>(c, fb, grid, st, map); break;
+        case 16: launch_fold<BF16, 16>(c, fb, grid, st, map); break;
+        case 32: launch_fold<BF16, 32>(c, fb, grid, st, map); break;
+        default: launch_fold<BF16, 0>(c, fb, grid, st, map);
     }
-#undef SHADOW_CASE
 }
 
 WdMap wd_map(const shadow_ctx* c) { return WdMap{c->d_tile_mode, c->d_run_start, c->d_run_flag, c->num_runs}; }
@@ -261,6 +250,62 @@ int32_t mark_boundary(shadow_ctx* c)
 {
     HIP_TRY(hipEventRecord(c->boundary_ev, c->streams[0]));
     c->boundary_pending = true;
+    return SHADOW_OK;
+}
+
+// Launch everything buffered for stream sid: as few launches as the descriptor allows.
+int32_t flush_stream(shadow_ctx* c, uint32_t sid)
+{
+    std::vector<shadow_ctx::Pending>& q = c->pending[sid];
+    if (q.empty()) return SHADOW_OK;
+    hipStream_t st = c->streams[sid];
+    const uint32_t W = c->hp.num_workers;
+    const WdMap map = wd_map(c);
+    size_t i = 0;
+    while (i < q.size()) {
+        FoldBatch fb{};
+        fb.w = W;
+        uint64_t blocks = 0;
+        uint32_t k = 0;
+        while (i < q.size() && k < kMaxBatch && (k + 1) * W <= kMaxBatchPtrs) {
+            const BucketL& b = c->lay.buckets[q[i].bucket];
+            const uint64_t nb = blocks_for(bucket_threads(b.numel), c->fold_block);
+            if (k > 0 && (blocks + nb) * c->fold_block > kMaxThreadsPerLaunch) break;
+            fb.first_block[k] = uint32_t(blocks);
+            fb.numel[k] = b.numel;
+            fb.arena_off[k] = b.arena_off;
+            fb.slot_base[k] = c->clip ? c->slot_base[q[i].bucket] : 0u;
+            for (uint32_t w = 0; w < W; ++w) fb.ptr[k * W + w] = q[i].ptr[w];
+            blocks += nb;
+            ++k;
+            ++i;
+        }
+        fb.count = k;
+        const uint32_t grid = uint32_t(blocks);
+        for (uint32_t j = k; j <= kMaxBatch; ++j) fb.first_block[j] = kNoBucket;   // "no bucket starts here"
+        ProfScope ps(c, c->clip ? SHADOW_K_FOLD_SUMSQ : SHADOW_K_FOLD_ADAMW, st);
+        if (ps.rc != SHADOW_OK) return ps.rc;
+        if (c->hp.grad_dtype == SHADOW_GRAD_BF16) dispatch_fold<true>(c, fb, grid, st, map);
+        else dispatch_fold<false>(c, fb, grid, st, map);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            g_hip_error = std::string("fold kernel launch: ") + hipGetErrorString(e);
+            return SHADOW_EHIP;
+        }
+        if (ps.end() != SHADOW_OK) return SHADOW_EHIP;
+    }
+    q.clear();
+    c->pending_bytes[sid] = 0;
+    c->stream_dirty[sid] = 1;
+    return SHADOW_OK;
+}
+
+int32_t flush_all(shadow_ctx* c)
+{
+    for (uint32_t s = 0; s < c->streams.size(); ++s) {
+        const int32_t rc = flush_stream(c, s);
+        if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+    }
     return SHADOW_OK;
 }
 
@@ -437,6 +482,49 @@ int32_t shadow_layout_tensor(const shadow_layout* L, uint32_t tensor, uint32_t* 
     return SHADOW_OK;
 }
 
+int32_t shadow_layout_arena_stride(const shadow_layout* L, uint64_t* stride_bytes)
+{
+    if (!L || !stride_bytes) return SHADOW_EINVAL;
+    uint64_t s = 2ull << 20;
+    while (s < L->arena_numel * sizeof(float)) s <<= 1;
+    *stride_bytes = s;
+    return SHADOW_OK;
+}
+
+namespace {
+uint64_t staging_view_stride(const shadow_layout* L, uint32_t bucket)
+{
+    const uint64_t bytes = L->buckets[bucket].numel * L->grad_elem_bytes;
+    const uint64_t a = bytes >= (2ull << 20) ? (2ull << 20) : 256ull;
+    return (bytes + a - 1) / a * a;
+}
+uint64_t staging_bucket_start(const shadow_layout* L, uint32_t num_workers, uint32_t bucket)
+{
+    uint64_t off = 0;
+    for (uint32_t b = 0; b < bucket; ++b) {
+        off += staging_view_stride(L, b) * num_workers;
+        off = (off + (2ull << 20) - 1) & ~((2ull << 20) - 1);
+    }
+    return off;
+}
+}  // namespace
+
+int32_t shadow_layout_staging_bytes(const shadow_layout* L, uint32_t num_workers, uint64_t* bytes)
+{
+    if (!L || !bytes || num_workers < 1 || num_workers > SHADOW_MAX_WORKERS) return SHADOW_EINVAL;
+    *bytes = staging_bucket_start(L, num_workers, uint32_t(L->buckets.size()));
+    return SHADOW_OK;
+}
+
+int32_t shadow_layout_staging_view(const shadow_layout* L, uint32_t num_workers, uint32_t bucket, uint32_t worker,
+                                   uint64_t* byte_offset)
+{
+    if (!L || !byte_offset || num_workers < 1 || num_workers > SHADOW_MAX_WORKERS || worker >= num_workers) return SHADOW_EINVAL;
+    if (bucket >= L->buckets.size()) return SHADOW_EBUCKET;
+    *byte_offset = staging_bucket_start(L, num_workers, bucket) + staging_view_stride(L, bucket) * worker;
+    return SHADOW_OK;
+}
+
 int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_hparams* hp, float* d_param, float* d_m,
                     float* d_v, float* d_reduced, uint64_t start_step, void* const* streams)
 {
@@ -470,10 +558,14 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
         c->completed = start_step;
         c->fold_block = uint32_t(g_tune.fold_block);
         c->adamw_block = uint32_t(g_tune.adamw_block);
+        c->fold_lds = uint32_t(g_tune.fold_lds);
+        c->adamw_lds = uint32_t(g_tune.adamw_lds);
         c->arrived.assign(layout->buckets.size(), 0);
         c->stream_dirty.assign(hp->num_streams, 0);
         c->streams.assign(hp->num_streams, nullptr);
         c->join_ev.assign(hp->num_streams, nullptr);
+        c->pending.assign(hp->num_streams, {});
+        c->pending_bytes.assign(hp->num_streams, 0);
     } catch (const std::bad_alloc&) {
         delete c;
         return SHADOW_ENOMEM;
@@ -514,16 +606,16 @@ int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const
     if (step != c->completed + 1) return SHADOW_ESTEP;
     if (c->arrived[bucket_id]) return SHADOW_EDUP;
     const uint32_t W = c->hp.num_workers;
-    GradViews gv{};
+    shadow_ctx::Pending pend{};
+    pend.bucket = bucket_id;
     for (uint32_t w = 0; w < W; ++w) {
         if (!d_grad_views[w] || !aligned(d_grad_views[w], 16)) return SHADOW_EINVAL;
-        gv.ptr[w] = d_grad_views[w];
+        pend.ptr[w] = d_grad_views[w];
     }
-    // ---- nothing above changed any state; from here on work is enqueued ----
+    // ---- nothing above changed any state; from here on work is buffered or enqueued ----
     const BucketL& b = c->lay.buckets[bucket_id];
     const uint32_t S = uint32_t(c->streams.size());
     const uint32_t sid = bucket_id % S;
-    hipStream_t st = c->streams[sid];
     auto hip_fail = [&](const char* what, hipError_t e) {
         g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
         c->poisoned = true;
@@ -540,16 +632,21 @@ int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const
             c->boundary_pending = false;
         }
     }
-    const WdMap map = wd_map(c);
-    {
-        ProfScope ps(c, c->clip ? SHADOW_K_FOLD_SUMSQ : SHADOW_K_FOLD_ADAMW, st);
-        if (ps.rc != SHADOW_OK) { c->poisoned = true; return ps.rc; }
-        if (c->hp.grad_dtype == SHADOW_GRAD_BF16) dispatch_fold<true>(c, gv, b, bucket_id, st, map);
-        else dispatch_fold<false>(c, gv, b, bucket_id, st, map);
-        if ((e = hipGetLastError()) != hipSuccess) return hip_fail("fold kernel launch", e);
-        if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
+    try {
+        c->pending[sid].push_back(pend);
+    } catch (const std::bad_alloc&) {
+        return SHADOW_ENOMEM;
     }
-    c->stream_dirty[sid] = 1;
+    c->pending_bytes[sid] += b.numel * c->lay.grad_elem_bytes * W;
+    const bool last = c->arrived_count + 1 == c->lay.buckets.size();
+    if (last) {
+        const int32_t rc = flush_all(c);
+        if (rc != SHADOW_OK) return rc;
+    } else if (c->pending_bytes[sid] >= c->hp.batch_bytes) {
+        const int32_t rc = flush_stream(c, sid);
+        if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+    }
+    const WdMap map = wd_map(c);
     c->arrived[bucket_id] = 1;
     c->arrived_count++;
     if (c->arrived_count == c->lay.buckets.size()) {
@@ -573,7 +670,7 @@ int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const
                 const uint64_t blocks = (nvec + c->adamw_block - 1) / c->adamw_block;
                 for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
                     const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
-                    k_adamw<<<uint32_t(nb), c->adamw_block, 0, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc);
+                    k_adamw<<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc);
                 }
                 if ((e = hipGetLastError()) != hipSuccess) return hip_fail("adamw kernel launch", e);
                 if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
@@ -610,6 +707,10 @@ int32_t shadow_snapshot(shadow_ctx* c, float* dst_param, float* dst_m, float* ds
 int32_t shadow_sync(shadow_ctx* c)
 {
     if (!c) return SHADOW_EINVAL;
+    if (!c->poisoned) {
+        const int32_t rc = flush_all(c);
+        if (rc != SHADOW_OK) return rc;
+    }
     for (hipStream_t s : c->streams) HIP_TRY(hipStreamSynchronize(s));
     return SHADOW_OK;
 }
@@ -617,6 +718,7 @@ int32_t shadow_sync(shadow_ctx* c)
 int32_t shadow_destroy(shadow_ctx* c)
 {
     if (!c) return SHADOW_OK;
+    if (!c->poisoned) (void)flush_all(c);     // buffered buckets were accepted: their work is owed
     for (hipStream_t s : c->streams) (void)hipStreamSynchronize(s);
     free_ctx(c);
     return SHADOW_OK;
@@ -722,9 +824,12 @@ const char* shadow_last_hip_error(void) { return g_hip_error.c_str(); }
 int32_t shadow_set_tunable(const char* name, int64_t value)
 {
     if (!name) return SHADOW_EINVAL;
-    if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return SHADOW_EINVAL;
-    if (!std::strcmp(name, "fold_block")) g_tune.fold_block = value;
-    else if (!std::strcmp(name, "adamw_block")) g_tune.adamw_block = value;
+    const bool is_block = value == 64 || value == 128 || value == 256 || value == 512 || value == 1024;
+    const bool is_lds = value >= 0 && value <= 65536 && value % 512 == 0;
+    if (!std::strcmp(name, "fold_block") && is_block) g_tune.fold_block = value;
+    else if (!std::strcmp(name, "adamw_block") && is_block) g_tune.adamw_block = value;
+    else if (!std::strcmp(name, "fold_lds") && is_lds) g_tune.fold_lds = value;
+    else if (!std::strcmp(name, "adamw_lds") && is_lds) g_tune.adamw_lds = value;
     else return SHADOW_EINVAL;
     return SHADOW_OK;
 }

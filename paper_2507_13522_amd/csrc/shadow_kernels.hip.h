@@ -42,9 +42,34 @@ constexpr int kMaxBlock = 1024;
 constexpr int kMaxWorkers = 64;
 constexpr int kWdTileShift = 10;     // weight-decay map granularity: 1024 elements
 
-struct GradViews {
-    const void* ptr[kMaxWorkers];
+// One launch folds a batch of buckets.  The descriptor travels in the kernel
+// arguments (no device table to keep coherent with the host): bucket k of the
+// batch owns blocks [first_block[k], first_block[k+1]) and its W view pointers
+// are ptr[k*w .. k*w+w).
+constexpr int kMaxBatch = 32;
+constexpr int kMaxBatchPtrs = 320;
+struct FoldBatch {
+    uint32_t count;
+    uint32_t w;
+    uint32_t first_block[kMaxBatch + 1];
+    uint32_t slot_base[kMaxBatch];      // first norm-partial slot of the bucket (clipping on)
+    uint64_t numel[kMaxBatch];
+    uint64_t arena_off[kMaxBatch];      // arena index of the bucket's first element
+    const void* ptr[kMaxBatchPtrs];
 };
+
+// Unused first_block entries hold 0x7FFFFFFF (block indices stay below 2^31), so the bucket
+// of a block is the number of entries 1..kMaxBatch-1 that are <= the block index, read off
+// the sign bits of (block - entry): two wide scalar loads and a chain of scalar ALU ops, no
+// dependent memory round trips before the wave can issue its loads.
+constexpr uint32_t kNoBucket = 0x7FFFFFFFu;
+__device__ __forceinline__ uint32_t bucket_of_block(const FoldBatch& fb, uint32_t block)
+{
+    uint32_t above = 0;
+#pragma unroll
+    for (int j = 1; j < kMaxBatch; ++j) above += (block - fb.first_block[j]) >> 31;
+    return uint32_t(kMaxBatch - 1) - above;
+}
 
 // Per-iteration scalars, prepared on the host in double and rounded once to float.
 struct StepScalars {
@@ -110,20 +135,20 @@ __device__ __forceinline__ void widen_add(const u32x2& a, f32x4& r)
 }
 
 template <bool BF16, int W>
-__device__ __forceinline__ f32x4 fold4(const GradViews& gv, uint32_t w_rt, uint64_t vec, const StepScalars& s)
+__device__ __forceinline__ f32x4 fold4(const void* const* vp, uint32_t w_rt, uint64_t vec, const StepScalars& s)
 {
     f32x4 r;
     if constexpr (BF16) {
         if constexpr (W > 0) {
             u32x2 raw[W];
 #pragma unroll
-            for (int w = 0; w < W; ++w) raw[w] = load_once(reinterpret_cast<const u32x2*>(gv.ptr[w]) + vec);
+            for (int w = 0; w < W; ++w) raw[w] = load_once(reinterpret_cast<const u32x2*>(vp[w]) + vec);
             widen_first(raw[0], r);
 #pragma unroll
             for (int w = 1; w < W; ++w) widen_add(raw[w], r);
         } else {
-            widen_first(load_once(reinterpret_cast<const u32x2*>(gv.ptr[0]) + vec), r);
-            for (uint32_t w = 1; w < w_rt; ++w) widen_add(load_once(reinterpret_cast<const u32x2*>(gv.ptr[w]) + vec), r);
+            widen_first(load_once(reinterpret_cast<const u32x2*>(vp[0]) + vec), r);
+            for (uint32_t w = 1; w < w_rt; ++w) widen_add(load_once(reinterpret_cast<const u32x2*>(vp[w]) + vec), r);
         }
     } else {
         if constexpr (W > 0) {
@@ -133,7 +158,7 @@ __device__ __forceinline__ f32x4 fold4(const GradViews& gv, uint32_t w_rt, uint6
                 f32x4 raw[kBatch];
 #pragma unroll
                 for (int j = 0; j < kBatch; ++j)
-                    if (w0 + j < W) raw[j] = load_once(reinterpret_cast<const f32x4*>(gv.ptr[w0 + j]) + vec);
+                    if (w0 + j < W) raw[j] = load_once(reinterpret_cast<const f32x4*>(vp[w0 + j]) + vec);
 #pragma unroll
                 for (int j = 0; j < kBatch; ++j) {
                     if (w0 + j < W) {
@@ -142,8 +167,8 @@ __device__ __forceinline__ f32x4 fold4(const GradViews& gv, uint32_t w_rt, uint6
                 }
             }
         } else {
-            r = load_once(reinterpret_cast<const f32x4*>(gv.ptr[0]) + vec);
-            for (uint32_t w = 1; w < w_rt; ++w) r = r + load_once(reinterpret_cast<const f32x4*>(gv.ptr[w]) + vec);
+            r = load_once(reinterpret_cast<const f32x4*>(vp[0]) + vec);
+            for (uint32_t w = 1; w < w_rt; ++w) r = r + load_once(reinterpret_cast<const f32x4*>(vp[w]) + vec);
         }
     }
     if (s.mean) r = r * s.inv_w;
@@ -152,16 +177,16 @@ __device__ __forceinline__ f32x4 fold4(const GradViews& gv, uint32_t w_rt, uint6
 
 // one element (ragged tail of a bucket)
 template <bool BF16>
-__device__ __forceinline__ float fold1(const GradViews& gv, uint32_t w_rt, uint64_t e, const StepScalars& s)
+__device__ __forceinline__ float fold1(const void* const* vp, uint32_t w_rt, uint64_t e, const StepScalars& s)
 {
     float acc;
     if constexpr (BF16) {
-        acc = bits_to_float(uint32_t(reinterpret_cast<const uint16_t*>(gv.ptr[0])[e]) << 16);
+        acc = bits_to_float(uint32_t(reinterpret_cast<const uint16_t*>(vp[0])[e]) << 16);
         for (uint32_t w = 1; w < w_rt; ++w)
-            acc = acc + bits_to_float(uint32_t(reinterpret_cast<const uint16_t*>(gv.ptr[w])[e]) << 16);
+            acc = acc + bits_to_float(uint32_t(reinterpret_cast<const uint16_t*>(vp[w])[e]) << 16);
     } else {
-        acc = reinterpret_cast<const float*>(gv.ptr[0])[e];
-        for (uint32_t w = 1; w < w_rt; ++w) acc = acc + reinterpret_cast<const float*>(gv.ptr[w])[e];
+        acc = reinterpret_cast<const float*>(vp[0])[e];
+        for (uint32_t w = 1; w < w_rt; ++w) acc = acc + reinterpret_cast<const float*>(vp[w])[e];
     }
     if (s.mean) acc = acc * s.inv_w;
     return acc;
@@ -189,57 +214,63 @@ __device__ __forceinline__ void adamw4(float* p, float* m, float* v, uint64_t ve
 }
 
 // ---- kernel: fold + AdamW in one pass (clipping off) ---------------------------------
-// p, m, v point at the bucket's first element; arena_off is that element's arena index.
-// Thread i < n/4 owns elements 4i..4i+3; thread n/4 owns the (n mod 4) tail elements.
+// p, m, v are the arenas.  Within its bucket, thread i < n/4 owns elements 4i..4i+3 and
+// thread n/4 owns the (n mod 4) tail elements.
 template <bool BF16, int W>
-__global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(GradViews gv, uint32_t w_rt, float* __restrict__ p,
-                                                          float* __restrict__ m, float* __restrict__ v, uint64_t n,
-                                                          uint64_t arena_off, WdMap map, StepScalars s)
+__global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* __restrict__ p, float* __restrict__ m,
+                                                          float* __restrict__ v, WdMap map, StepScalars s)
 {
+    const uint32_t k = bucket_of_block(fb, blockIdx.x);
+    const void* const* vp = fb.ptr + k * fb.w;
+    const uint64_t n = fb.numel[k], off = fb.arena_off[k];
     const uint64_t nvec = n >> 2;
-    const uint64_t vec = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const uint64_t vec = uint64_t(blockIdx.x - fb.first_block[k]) * blockDim.x + threadIdx.x;
     if (vec < nvec) {
-        const f32x4 r = fold4<BF16, W>(gv, w_rt, vec, s);
-        adamw4(p, m, v, vec, arena_off + (vec << 2), r, map, s);
+        const f32x4 r = fold4<BF16, W>(vp, fb.w, vec, s);
+        adamw4(p + off, m + off, v + off, vec, off + (vec << 2), r, map, s);
     } else if (vec == nvec) {
         for (uint64_t e = nvec << 2; e < n; ++e) {
-            float g = fold1<BF16>(gv, w_rt, e, s);
-            float pp = p[e], mm = m[e], vv = v[e];
-            adamw_elem(pp, mm, vv, g, decay_factor_of(map, arena_off + e, s.decay), s);
-            p[e] = pp; m[e] = mm; v[e] = vv;
+            float g = fold1<BF16>(vp, fb.w, e, s);
+            float pp = p[off + e], mm = m[off + e], vv = v[off + e];
+            adamw_elem(pp, mm, vv, g, decay_factor_of(map, off + e, s.decay), s);
+            p[off + e] = pp; m[off + e] = mm; v[off + e] = vv;
         }
     }
 }
 
 // ---- kernel: fold + sum of squares, reduced gradient stored (clipping on) -------------
-// r_out points at the bucket's first scratch element.  Every wave writes the sum of its
-// lanes' squares to its own slot, partial[global wave index]: no barrier, fixed order.
+// r is the scratch arena.  Every wave writes the sum of its lanes' squares to its own slot,
+// partial[slot_base of the bucket + wave index within the bucket]: no barrier, fixed order.
 template <bool BF16, int W>
-__global__ __launch_bounds__(kMaxBlock) void k_fold_sumsq(GradViews gv, uint32_t w_rt, float* __restrict__ r_out, uint64_t n,
-                                                          double* __restrict__ partial, StepScalars s)
+__global__ __launch_bounds__(kMaxBlock) void k_fold_sumsq(FoldBatch fb, float* __restrict__ r, double* __restrict__ partial,
+                                                          StepScalars s)
 {
+    const uint32_t k = bucket_of_block(fb, blockIdx.x);
+    const void* const* vp = fb.ptr + k * fb.w;
+    const uint64_t n = fb.numel[k];
+    float* r_out = r + fb.arena_off[k];
     const uint64_t nvec = n >> 2;
-    const uint64_t vec = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    const uint64_t vec = uint64_t(blockIdx.x - fb.first_block[k]) * blockDim.x + threadIdx.x;
     double acc = 0.0;
     if (vec < nvec) {
-        const f32x4 r = fold4<BF16, W>(gv, w_rt, vec, s);
-        store_once(reinterpret_cast<f32x4*>(r_out) + vec, r);
+        const f32x4 rr = fold4<BF16, W>(vp, fb.w, vec, s);
+        store_once(reinterpret_cast<f32x4*>(r_out) + vec, rr);
 #pragma unroll
-        for (int k = 0; k < kVec; ++k) {
-            const double d = double(r[k]);
+        for (int j = 0; j < kVec; ++j) {
+            const double d = double(rr[j]);
             acc = fma(d, d, acc);        // d*d is exact in double, so this equals acc + d*d
         }
     } else if (vec == nvec) {
         for (uint64_t e = nvec << 2; e < n; ++e) {
-            const float g = fold1<BF16>(gv, w_rt, e, s);
+            const float g = fold1<BF16>(vp, fb.w, e, s);
             r_out[e] = g;
             const double d = double(g);
             acc = fma(d, d, acc);
         }
     }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-    if ((threadIdx.x & 63) == 0) partial[vec >> 6] = acc;
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) partial[fb.slot_base[k] + (vec >> 6)] = acc;
 }
 
 // ---- block-wide sum of doubles in a fixed order ----------------------------------------

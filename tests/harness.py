@@ -20,6 +20,9 @@ import paper_2507_13522_amd as sh
 import synth
 
 TILE_PERIOD = 1_000_003          # prime
+# launch configuration that bench.py times (and the full-size parity test repeats)
+BENCH_STREAMS = 1
+BENCH_BATCH_BYTES = 4 << 30
 
 
 class Inputs:
@@ -120,11 +123,12 @@ def lib_layout(wl: synth.Workload) -> sh.Layout:
                      wl.explicit_buckets)
 
 
-def lib_hparams(wl: synth.Workload, num_streams: int = 2, mean: bool = True) -> sh.HParams:
+def lib_hparams(wl: synth.Workload, num_streams: int = 2, mean: bool = True, batch_bytes: int = 0) -> sh.HParams:
     return sh.HParams(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay,
                       max_grad_norm=wl.max_grad_norm, num_workers=wl.num_workers,
                       grad_dtype=sh.GRAD_BF16 if wl.grad_dtype == "bf16" else sh.GRAD_F32,
-                      reduce_op=sh.REDUCE_MEAN if mean else sh.REDUCE_SUM, num_streams=num_streams)
+                      reduce_op=sh.REDUCE_MEAN if mean else sh.REDUCE_SUM, num_streams=num_streams,
+                      batch_bytes=batch_bytes)
 
 
 def assert_layouts_agree(ol: oracle.Layout, ll: sh.Layout) -> None:
@@ -144,7 +148,8 @@ class GpuShadow:
     """The library on cuda:0 over torch-allocated arenas, with every bucket's W views resident."""
 
     def __init__(self, wl: synth.Workload, inputs: Inputs, num_streams: int = 2, mean: bool = True,
-                 torch_streams: bool = False, resident_grads: bool = True, init_from=None, start_step: int = 0):
+                 torch_streams: bool = False, resident_grads: bool = True, init_from=None, start_step: int = 0,
+                 advised_placement: bool = True, batch_bytes: int = 0):
         assert torch.cuda.is_available()
         self.wl, self.inputs = wl, inputs
         self.dev = torch.device("cuda:0")
@@ -157,21 +162,29 @@ class GpuShadow:
             self.logical_start.append(acc)
             acc += n
         A = L.arena_numel
-        self.p = torch.empty(A, dtype=torch.float32, device=self.dev)
-        self.m = torch.zeros(A, dtype=torch.float32, device=self.dev)
-        self.v = torch.zeros(A, dtype=torch.float32, device=self.dev)
-        self.r = torch.empty(A, dtype=torch.float32, device=self.dev) if wl.max_grad_norm > 0 else None
+        clip = wl.max_grad_norm > 0
+        # placement follows the library's advice: the arenas are carved from ONE allocation, a power-of-two
+        # stride apart; the gradient views sit in a bucket-major staging buffer
+        stride = L.arena_stride() if advised_placement else (A * 4 + 255) // 256 * 256
+        narr = 4 if clip else 3
+        self._state = torch.empty((narr - 1) * stride + A * 4, dtype=torch.uint8, device=self.dev)
+        arenas = [self._state[k * stride:k * stride + A * 4].view(torch.float32) for k in range(narr)]
+        self.p, self.m, self.v = arenas[:3]
+        self.r = arenas[3] if clip else None
+        self.m.zero_()
+        self.v.zero_()
         if init_from is None:
             for (off, n, _), ls in zip(self.buckets, self.logical_start):
                 inputs.fill_param_dev(self.p[off:off + n], ls)
         else:
             self.p.copy_(init_from[0]); self.m.copy_(init_from[1]); self.v.copy_(init_from[2])
         gdt = torch.int16 if wl.grad_dtype == "bf16" else torch.float32
-        self.grads = None
-        if resident_grads:
-            self.grads = [torch.empty(A, dtype=gdt, device=self.dev) for _ in range(wl.num_workers)]
         self.gdt = gdt
-        self.hp = lib_hparams(wl, num_streams, mean)
+        W = wl.num_workers
+        self._stage = None
+        if resident_grads:
+            self._stage = torch.empty(max(L.staging_bytes(W), 256), dtype=torch.uint8, device=self.dev)
+        self.hp = lib_hparams(wl, num_streams, mean, batch_bytes)
         self._tstreams = [torch.cuda.Stream(device=self.dev) for _ in range(num_streams)] if torch_streams else None
         torch.cuda.synchronize()
         self.ctx = sh.Shadow(L, self.hp, self.p.data_ptr(), self.m.data_ptr(), self.v.data_ptr(),
@@ -179,13 +192,19 @@ class GpuShadow:
                              [s.cuda_stream for s in self._tstreams] if self._tstreams else None)
         self._views = None
         if resident_grads:
-            self._views = [self.ctx.views_array([g[off:off + n].data_ptr() for g in self.grads]) for off, n, _ in self.buckets]
+            self._views = [self.ctx.views_array([self.view(b, w).data_ptr() for w in range(W)])
+                           for b in range(len(self.buckets))]
+
+    def view(self, b: int, w: int) -> torch.Tensor:
+        """Worker w's gradient view of bucket b inside the staging buffer."""
+        n = self.buckets[b][1]
+        off = self.layout.staging_view(self.wl.num_workers, b, w)
+        return self._stage[off:off + n * self.wl.grad_bytes].view(self.gdt)
 
     def fill_grads(self, step: int, buckets: Optional[Sequence[int]] = None) -> None:
         for b in (range(len(self.buckets)) if buckets is None else buckets):
-            off, n, _ = self.buckets[b]
             for w in range(self.wl.num_workers):
-                self.inputs.fill_grad_dev(self.grads[w][off:off + n], step, w, self.logical_start[b])
+                self.inputs.fill_grad_dev(self.view(b, w), step, w, self.logical_start[b])
         torch.cuda.synchronize()
 
     def apply_step(self, step: int, order: Optional[Sequence[int]] = None) -> None:

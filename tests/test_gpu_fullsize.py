@@ -16,7 +16,7 @@ import torch
 
 import oracle
 import synth
-from harness import (GpuShadow, Inputs, TILE_PERIOD, assert_layouts_agree, assert_state_matches, lib_layout,
+from harness import (BENCH_BATCH_BYTES, BENCH_STREAMS, GpuShadow, Inputs, TILE_PERIOD, assert_layouts_agree, assert_state_matches, lib_layout,
                      oracle_hparams, oracle_layout)
 
 pytestmark = pytest.mark.gpu
@@ -54,7 +54,8 @@ def pick_buckets(lay: oracle.Layout, budget: int):
     return sorted(out)
 
 
-def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resident: bool, num_streams: int = 2):
+def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resident: bool, num_streams: int = 2,
+                 batch_bytes: int = 0):
     wl = synth.get_workload(name)
     say(f"case fullsize {name}: P={wl.num_params} W={wl.num_workers} steps={steps}")
     t_start = time.time()
@@ -68,7 +69,7 @@ def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resi
     clip = wl.max_grad_norm > 0
     W = wl.num_workers
 
-    g = GpuShadow(wl, inp, num_streams=num_streams, resident_grads=resident)
+    g = GpuShadow(wl, inp, num_streams=num_streams, resident_grads=resident, batch_bytes=batch_bytes)
     B = len(g.buckets)
     ring = None
     if not resident:
@@ -168,7 +169,13 @@ def test_gpt_1p3b_full():
 
 
 def test_llama7b_full():
-    run_fullsize("llama7b", steps=5, bucket_budget=60_000_000, n_scatter=500_000, resident=True)
+    """Same launch configuration as bench.py: one stream, the iteration's buckets folded in as few launches as possible."""
+    run_fullsize("llama7b", steps=5, bucket_budget=60_000_000, n_scatter=500_000, resident=True, num_streams=BENCH_STREAMS,
+                 batch_bytes=BENCH_BATCH_BYTES)
+
+
+def test_llama7b_full_one_launch_per_bucket():
+    run_fullsize("llama7b", steps=2, bucket_budget=60_000_000, n_scatter=500_000, resident=True, num_streams=2, batch_bytes=0)
 
 
 def test_ragged7b_full():

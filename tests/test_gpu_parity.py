@@ -28,12 +28,13 @@ def custom(name, sizes_flags, W, dtype, clip=0.0, cap=1 << 16, steps=3, dist="no
                           random_arrival=random_arrival, lr=lr)
 
 
-def check_against_oracle(wl, steps=None, num_streams=2, mean=True, every_step=True, exact=True, torch_streams=False):
+def check_against_oracle(wl, steps=None, num_streams=2, mean=True, every_step=True, exact=True, torch_streams=False,
+                         batch_bytes=0):
     """Run both sides on the same inputs and compare param, m, v of every bucket."""
     steps = steps or wl.steps
     inp = Inputs(wl)
     assert_layouts_agree(oracle_layout(wl), lib_layout(wl))
-    g = GpuShadow(wl, inp, num_streams=num_streams, mean=mean, torch_streams=torch_streams)
+    g = GpuShadow(wl, inp, num_streams=num_streams, mean=mean, torch_streams=torch_streams, batch_bytes=batch_bytes)
     worst = {}
 
     def on_step(t, orc):
@@ -67,12 +68,25 @@ RAGGED = [(5000, True), (33, False), (70001, True), (1, False), (64, True), (123
           (2048, False), (77777, True), (7, True), (3, False), (5, True), (1024, True), (8, False)]
 
 
+@pytest.mark.parametrize("batch_bytes", [0, 1 << 20, 1 << 62])
 @pytest.mark.parametrize("W,dtype", [(3, "bf16"), (8, "bf16"), (5, "f32")])
-def test_ragged_clip_random_arrival(W, dtype):
-    """Several tiles, ragged tails, flags changing inside a vector, clipping active, shuffled bucket arrival."""
-    say("case ragged", W, dtype)
+def test_ragged_clip_random_arrival(W, dtype, batch_bytes):
+    """Several tiles, ragged tails, flags changing inside a vector, clipping active, shuffled bucket arrival;
+    every bucket its own launch, a few buckets per launch, and the whole iteration in as few launches as possible."""
+    say("case ragged", W, dtype, batch_bytes)
     wl = custom("ragged", RAGGED, W, dtype, clip=0.01, cap=200_000, steps=5, random_arrival=True)
-    check_against_oracle(wl, num_streams=3)
+    check_against_oracle(wl, num_streams=3, batch_bytes=batch_bytes)
+
+
+@pytest.mark.parametrize("W,dtype,clip", [(64, "bf16", 0.0), (64, "f32", 0.01), (16, "bf16", 0.01), (2, "bf16", 0.0)])
+def test_many_small_buckets_batched(W, dtype, clip):
+    """More buckets than one launch descriptor holds (32 buckets / 320 pointers): batches split correctly."""
+    say("case many buckets", W, dtype, clip)
+    rng = np.random.default_rng(W)
+    sizes = [(int(n), bool(f)) for n, f in zip(rng.integers(1, 3000, 150), rng.integers(0, 2, 150))]
+    wl = custom("many", sizes, W, dtype, clip=clip, cap=4000, steps=2, random_arrival=True)
+    for streams, bb in ((1, 1 << 62), (3, 1 << 62), (2, 100_000)):
+        check_against_oracle(wl, num_streams=streams, batch_bytes=bb)
 
 
 @pytest.mark.parametrize("W", [1, 2, 4, 6, 8, 16, 32, 64])
@@ -195,7 +209,7 @@ def test_order_partition_and_stream_invariance():
                 b, ob, oa = per_tensor[t]
                 n = sizes[t][0]
                 for w in range(4):
-                    g.grads[w][oa:oa + n].copy_(inp.grad_at(step, w, torch.arange(base[t], base[t] + n)))
+                    g.view(b, w)[ob:ob + n].copy_(inp.grad_at(step, w, torch.arange(base[t], base[t] + n)))
             torch.cuda.synchronize()
             order = synth.arrival_order(5, step, len(g.buckets)) if shuffle else None
             g.apply_step(step, order)
@@ -216,8 +230,8 @@ def test_clip_arrival_order_invariance():
     say("case clip order invariance")
     wl = custom("inv-clip", RAGGED, 8, "bf16", clip=0.01, cap=100_000, steps=3)
     outs = []
-    for shuffle, streams in [(False, 1), (True, 4), (True, 2)]:
-        g = GpuShadow(wl, Inputs(wl), num_streams=streams)
+    for shuffle, streams, bb in [(False, 1, 0), (True, 4, 0), (True, 2, 1 << 62), (False, 3, 300_000)]:
+        g = GpuShadow(wl, Inputs(wl), num_streams=streams, batch_bytes=bb)
         for step in range(1, 4):
             g.run_step(step, synth.arrival_order(11 + streams, step, len(g.buckets)) if shuffle else None)
         outs.append((g.p.clone(), g.m.clone(), g.v.clone(), g.ctx.clip_state()))
@@ -288,10 +302,9 @@ def test_exactly_once_errors_leave_state_untouched():
     assert g.ctx.try_apply_bucket(B, v0, 1) == binding.EBUCKET
     assert g.ctx.try_apply_bucket(0, v0, 2) == binding.ESTEP
     assert g.ctx.try_apply_bucket(0, v0, 0) == binding.ESTEP
-    off, n, _ = g.buckets[0]
-    misaligned = g.ctx.views_array([g.grads[0][off + 1:].data_ptr(), g.grads[1][off:].data_ptr()])
+    misaligned = g.ctx.views_array([g.view(0, 0)[1:].data_ptr(), g.view(0, 1).data_ptr()])
     assert g.ctx.try_apply_bucket(0, misaligned, 1) == binding.EINVAL
-    assert g.ctx.try_apply_bucket(0, g.ctx.views_array([g.grads[0][off:].data_ptr(), 0]), 1) == binding.EINVAL
+    assert g.ctx.try_apply_bucket(0, g.ctx.views_array([g.view(0, 0).data_ptr(), 0]), 1) == binding.EINVAL
     g.ctx.sync()
     assert all(torch.equal(a, b) for a, b in zip(before, (g.p, g.m, g.v))) and g.ctx.step() == (0, 0)
     assert g.ctx.try_apply_bucket(0, v0, 1) == binding.OK

@@ -106,3 +106,26 @@ def test_null_handles_are_rejected():
     assert L.shadow_destroy(None) == binding.OK
     assert L.shadow_set_tunable(b"nope", 1) == binding.EINVAL
     assert L.shadow_copy_probe(None, None, 16, None) == binding.EINVAL
+
+
+def test_placement_advice():
+    wl = synth.get_workload("llama7b")
+    lay = lib_layout(wl)
+    assert lay.arena_stride() == 32 << 30                       # 25.1 GiB arena -> 32 GiB
+    W = wl.num_workers
+    total = lay.staging_bytes(W)
+    prev_end = 0
+    for b in range(lay.num_buckets):
+        n = lay.bucket(b)[1]
+        for w in range(W):
+            off = lay.staging_view(W, b, w)
+            assert off >= prev_end and off % (2 << 20 if n * 2 >= (2 << 20) else 256) == 0
+            prev_end = off + n * 2
+    assert prev_end <= total <= 1.03 * lay.num_params * 2 * W    # bucket-major, little padding
+    small = sh.Layout([(100, True), (7, False)], 4, 64)
+    assert small.arena_stride() == 2 << 20 and small.num_buckets == 2
+    assert small.staging_view(3, 0, 0) == 0 and small.staging_view(3, 0, 1) == 256 and small.staging_view(3, 1, 0) == 2 << 20
+    with pytest.raises(sh.ShadowError):
+        small.staging_view(3, 0, 3)
+    with pytest.raises(sh.ShadowError):
+        small.staging_view(3, 2, 0)
