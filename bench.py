@@ -49,9 +49,11 @@ def measured_traffic(workload: str, kernel: str):
 KERNEL_NAMES = {0: "k_fold_adamw", 1: "k_fold_sumsq", 2: "k_norm_finalize", 3: "k_adamw"}
 
 
-def algorithmic_bytes_per_param(wl) -> dict:
+def algorithmic_bytes_per_param(wl, refold: bool = False) -> dict:
     """Bytes the method must move per parameter and step, by kernel (measurement)."""
     g = wl.grad_bytes * wl.num_workers
+    if wl.max_grad_norm > 0 and refold:          # views folded twice, reduced gradient never stored
+        return {"k_fold_sumsq": g, "k_fold_adamw": g + 24, "total": 2 * g + 24}
     if wl.max_grad_norm > 0:
         return {"k_fold_sumsq": g + 4, "k_adamw": 4 + 24, "total": g + 32}
     return {"k_fold_adamw": g + 24, "total": g + 24}
@@ -112,6 +114,8 @@ def main() -> int:
     ap.add_argument("--batch-mib", type=int, default=None,
                     help="bucket scheduling: gradient MiB buffered per stream before one fold launch (0 = every bucket "
                          "its own launch; default: the whole iteration in as few launches as the descriptor allows)")
+    ap.add_argument("--refold", action="store_true",
+                    help="clipping without a scratch arena: fold the views twice instead of storing the reduced gradient")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fold-block", type=int, default=0)
     ap.add_argument("--adamw-block", type=int, default=0)
@@ -141,7 +145,7 @@ def main() -> int:
 
     wl = synth.get_workload(args.workload)
     inputs = Inputs(wl, period=TILE_PERIOD)
-    g = GpuShadow(wl, inputs, num_streams=streams, batch_bytes=batch_bytes)
+    g = GpuShadow(wl, inputs, num_streams=streams, batch_bytes=batch_bytes, refold=args.refold)
     P = g.layout.num_params
     g.fill_grads(1)            # the same resident views serve every timed step (values do not affect timing)
     step = 0
@@ -169,7 +173,7 @@ def main() -> int:
     g.ctx.profile_enable(False)
 
     ms_per_step = 1e3 * elapsed / args.steps
-    bpp = algorithmic_bytes_per_param(wl)
+    bpp = algorithmic_bytes_per_param(wl, args.refold)
     kernels = {}
     for kind, name in KERNEL_NAMES.items():
         n, ms = g.ctx.profile_read(kind)
@@ -203,7 +207,7 @@ def main() -> int:
                                f"AdamW" + (f" + global-norm clip at {wl.max_grad_norm}" if wl.max_grad_norm > 0 else ""),
                    "num_params": P, "num_buckets": len(g.buckets), "num_workers": wl.num_workers,
                    "grad_dtype": wl.grad_dtype, "streams": streams,
-                   "batch_bytes": batch_bytes},
+                   "batch_bytes": batch_bytes, "refold": bool(args.refold)},
         "hbm_GBps": total_gbs,
         "hbm_frac_of_peak": total_gbs / HBM_PEAK_GBS,
         "bytes_per_param": bpp["total"],

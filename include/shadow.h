@@ -152,6 +152,13 @@ typedef struct shadow_ctx shadow_ctx;
  *              holds the reduced gradient between the fold and the update when
  *              clipping is on (the norm over ALL buckets must be known before
  *              any element is updated).  Must be NULL when clipping is off.
+ *              May be NULL with clipping on: the library then folds every
+ *              bucket's views a second time once the norm is known instead of
+ *              storing the reduced gradient (24 + 2*W*G bytes per parameter
+ *              instead of 32 + W*G, G = gradient element size: fewer bytes when
+ *              W*G < 8, e.g. the paper's own case of ONE already-reduced bf16
+ *              gradient per bucket, W = 1); the views of the whole iteration
+ *              must then stay unchanged until its update has run.
  *   start_step iterations already applied to this state (0 for a fresh
  *              replica; a snapshot's step when restoring).  The first
  *              iteration applied is start_step + 1; Adam's bias correction

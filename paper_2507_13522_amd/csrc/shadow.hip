@@ -69,6 +69,8 @@ struct shadow_ctx {
     shadow_hparams hp;
     float *p = nullptr, *m = nullptr, *v = nullptr, *r = nullptr;
     bool clip = false;
+    bool refold = false;                  // clipping on without a scratch arena: views are folded twice
+    std::vector<const void*> step_views;  // refold: the iteration's view pointers, bucket-major
     std::vector<hipStream_t> streams;
     bool own_streams = false;
     // device tables owned by the library
@@ -186,6 +188,30 @@ uint32_t blocks_for(uint64_t threads, uint32_t block)
     return uint32_t(blocks ? blocks : 1);
 }
 
+// groups of 4 elements one lane of the fold + sum-of-squares kernel owns (mirrors fold_vpl in the kernels)
+uint32_t sumsq_vpl(const shadow_hparams& hp)
+{
+    const bool bf16 = hp.grad_dtype == SHADOW_GRAD_BF16;
+    switch (hp.num_workers) {
+        case 1: return bf16 ? fold_vpl<true, 1>() : fold_vpl<false, 1>();
+        case 2: return bf16 ? fold_vpl<true, 2>() : fold_vpl<false, 2>();
+        case 4: return bf16 ? fold_vpl<true, 4>() : fold_vpl<false, 4>();
+        case 8: return bf16 ? fold_vpl<true, 8>() : fold_vpl<false, 8>();
+        case 16: return bf16 ? fold_vpl<true, 16>() : fold_vpl<false, 16>();
+        case 32: return bf16 ? fold_vpl<true, 32>() : fold_vpl<false, 32>();
+        default: return 1;      // run-time worker count
+    }
+}
+
+// blocks of a bucket's launch: update == false is the fold + sum-of-squares kernel
+uint32_t bucket_blocks(const shadow_ctx* c, uint64_t numel, bool update);
+
+uint32_t bucket_blocks(const shadow_ctx* c, uint64_t numel, bool update)
+{
+    const uint32_t vpl = update ? 1u : sumsq_vpl(c->hp);
+    return blocks_for(bucket_threads(numel), c->fold_block * vpl);
+}
+
 int32_t get_event(shadow_ctx* c, hipEvent_t* out)
 {
     if (!c->ev_pool.empty()) { *out = c->ev_pool.back(); c->ev_pool.pop_back(); return SHADOW_OK; }
@@ -211,24 +237,29 @@ struct ProfScope {
     }
 };
 
+// update == false: the fold of an arriving bucket (with clipping: sum of squares, reduced gradient stored unless
+// re-fold mode).  update == true: fold + AdamW (clipping off: the only pass; re-fold mode: the second pass, scaled
+// by the clip coefficient).
 template <bool BF16, int W>
-void launch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map)
+void launch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map, bool update)
 {
-    if (c->clip) k_fold_sumsq<BF16, W><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->r, c->d_partial, c->sc);
-    else k_fold_adamw<BF16, W><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, map, c->sc);
+    if (update)
+        k_fold_adamw<BF16, W><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, c->clip ? c->d_coef : nullptr, map, c->sc);
+    else
+        k_fold_sumsq<BF16, W><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->r, c->d_partial, c->sc);
 }
 
 template <bool BF16>
-void dispatch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map)
+void dispatch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map, bool update)
 {
     switch (c->hp.num_workers) {
-        case 1: launch_fold<BF16, 1>(c, fb, grid, st, map); break;
-        case 2: launch_fold<BF16, 2>(c, fb, grid, st, map); break;
-        case 4: launch_fold<BF16, 4>(c, fb, grid, st, map); break;
-        case 8: launch_fold<BF16, 8>(c, fb, grid, st, map); break;
-        case 16: launch_fold<BF16, 16>(c, fb, grid, st, map); break;
-        case 32: launch_fold<BF16, 32>(c, fb, grid, st, map); break;
-        default: launch_fold<BF16, 0>(c, fb, grid, st, map);
+        case 1: launch_fold<BF16, 1>(c, fb, grid, st, map, update); break;
+        case 2: launch_fold<BF16, 2>(c, fb, grid, st, map, update); break;
+        case 4: launch_fold<BF16, 4>(c, fb, grid, st, map, update); break;
+        case 8: launch_fold<BF16, 8>(c, fb, grid, st, map, update); break;
+        case 16: launch_fold<BF16, 16>(c, fb, grid, st, map, update); break;
+        case 32: launch_fold<BF16, 32>(c, fb, grid, st, map, update); break;
+        default: launch_fold<BF16, 0>(c, fb, grid, st, map, update);
     }
 }
 
@@ -253,29 +284,29 @@ int32_t mark_boundary(shadow_ctx* c)
     return SHADOW_OK;
 }
 
-// Launch everything buffered for stream sid: as few launches as the descriptor allows.
-int32_t flush_stream(shadow_ctx* c, uint32_t sid)
+// Fold the given buckets on stream st in as few launches as the descriptor allows.
+// ptrs(i) yields the W view pointers of the i-th bucket of the list.
+template <typename PtrFn>
+int32_t launch_buckets(shadow_ctx* c, const uint32_t* ids, size_t count, PtrFn ptrs, hipStream_t st, bool update)
 {
-    std::vector<shadow_ctx::Pending>& q = c->pending[sid];
-    if (q.empty()) return SHADOW_OK;
-    hipStream_t st = c->streams[sid];
     const uint32_t W = c->hp.num_workers;
     const WdMap map = wd_map(c);
     size_t i = 0;
-    while (i < q.size()) {
+    while (i < count) {
         FoldBatch fb{};
         fb.w = W;
         uint64_t blocks = 0;
         uint32_t k = 0;
-        while (i < q.size() && k < kMaxBatch && (k + 1) * W <= kMaxBatchPtrs) {
-            const BucketL& b = c->lay.buckets[q[i].bucket];
-            const uint64_t nb = blocks_for(bucket_threads(b.numel), c->fold_block);
+        while (i < count && k < kMaxBatch && (k + 1) * W <= kMaxBatchPtrs) {
+            const BucketL& b = c->lay.buckets[ids[i]];
+            const uint64_t nb = bucket_blocks(c, b.numel, update);
             if (k > 0 && (blocks + nb) * c->fold_block > kMaxThreadsPerLaunch) break;
             fb.first_block[k] = uint32_t(blocks);
             fb.numel[k] = b.numel;
             fb.arena_off[k] = b.arena_off;
-            fb.slot_base[k] = c->clip ? c->slot_base[q[i].bucket] : 0u;
-            for (uint32_t w = 0; w < W; ++w) fb.ptr[k * W + w] = q[i].ptr[w];
+            fb.slot_base[k] = (c->clip && !update) ? c->slot_base[ids[i]] : 0u;
+            const void* const* vp = ptrs(i);
+            for (uint32_t w = 0; w < W; ++w) fb.ptr[k * W + w] = vp[w];
             blocks += nb;
             ++k;
             ++i;
@@ -283,10 +314,10 @@ int32_t flush_stream(shadow_ctx* c, uint32_t sid)
         fb.count = k;
         const uint32_t grid = uint32_t(blocks);
         for (uint32_t j = k; j <= kMaxBatch; ++j) fb.first_block[j] = kNoBucket;   // "no bucket starts here"
-        ProfScope ps(c, c->clip ? SHADOW_K_FOLD_SUMSQ : SHADOW_K_FOLD_ADAMW, st);
+        ProfScope ps(c, update ? SHADOW_K_FOLD_ADAMW : SHADOW_K_FOLD_SUMSQ, st);
         if (ps.rc != SHADOW_OK) return ps.rc;
-        if (c->hp.grad_dtype == SHADOW_GRAD_BF16) dispatch_fold<true>(c, fb, grid, st, map);
-        else dispatch_fold<false>(c, fb, grid, st, map);
+        if (c->hp.grad_dtype == SHADOW_GRAD_BF16) dispatch_fold<true>(c, fb, grid, st, map, update);
+        else dispatch_fold<false>(c, fb, grid, st, map, update);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             g_hip_error = std::string("fold kernel launch: ") + hipGetErrorString(e);
@@ -294,6 +325,19 @@ int32_t flush_stream(shadow_ctx* c, uint32_t sid)
         }
         if (ps.end() != SHADOW_OK) return SHADOW_EHIP;
     }
+    return SHADOW_OK;
+}
+
+// Launch everything buffered for stream sid.
+int32_t flush_stream(shadow_ctx* c, uint32_t sid)
+{
+    std::vector<shadow_ctx::Pending>& q = c->pending[sid];
+    if (q.empty()) return SHADOW_OK;
+    std::vector<uint32_t> ids(q.size());
+    for (size_t i = 0; i < q.size(); ++i) ids[i] = q[i].bucket;
+    const int32_t rc = launch_buckets(c, ids.data(), ids.size(), [&](size_t i) { return q[i].ptr; }, c->streams[sid],
+                                      /*update=*/!c->clip);
+    if (rc != SHADOW_OK) return rc;
     q.clear();
     c->pending_bytes[sid] = 0;
     c->stream_dirty[sid] = 1;
@@ -379,7 +423,7 @@ int32_t build_tables(shadow_ctx* c)
         for (size_t b = 0; b < L.buckets.size(); ++b) {
             c->slot_base[b] = uint32_t(total);
             // one slot per wave of the bucket's fold launch
-            c->slot_count[b] = blocks_for(bucket_threads(L.buckets[b].numel), c->fold_block) * (c->fold_block / 64);
+            c->slot_count[b] = bucket_blocks(c, L.buckets[b].numel, false) * (c->fold_block / 64);
             total += c->slot_count[b];
             if (total > 0x7FFFFFFFull) return SHADOW_EINVAL;
         }
@@ -540,7 +584,7 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
     if (hp->reduce_op != SHADOW_REDUCE_MEAN && hp->reduce_op != SHADOW_REDUCE_SUM) return SHADOW_EINVAL;
     if (hp->num_streams < 1 || hp->num_streams > SHADOW_MAX_STREAMS) return SHADOW_EINVAL;
     const bool clip = hp->max_grad_norm > 0.f;
-    if (clip != (d_reduced != nullptr)) return SHADOW_EINVAL;
+    if (!clip && d_reduced) return SHADOW_EINVAL;
     if (!aligned(d_param, 256) || !aligned(d_m, 256) || !aligned(d_v, 256) || !aligned(d_reduced, 256)) return SHADOW_EINVAL;
     if (d_param == d_m || d_param == d_v || d_m == d_v) return SHADOW_EINVAL;
 
@@ -555,6 +599,8 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
         c->hp = *hp;
         c->p = d_param; c->m = d_m; c->v = d_v; c->r = d_reduced;
         c->clip = clip;
+        c->refold = clip && !d_reduced;
+        if (c->refold) c->step_views.assign(layout->buckets.size() * size_t(hp->num_workers), nullptr);
         c->completed = start_step;
         c->fold_block = uint32_t(g_tune.fold_block);
         c->adamw_block = uint32_t(g_tune.adamw_block);
@@ -637,6 +683,8 @@ int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const
     } catch (const std::bad_alloc&) {
         return SHADOW_ENOMEM;
     }
+    if (c->refold)
+        for (uint32_t w = 0; w < W; ++w) c->step_views[size_t(bucket_id) * W + w] = pend.ptr[w];
     c->pending_bytes[sid] += b.numel * c->lay.grad_elem_bytes * W;
     const bool last = c->arrived_count + 1 == c->lay.buckets.size();
     if (last) {
@@ -662,7 +710,14 @@ int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const
                 if ((e = hipGetLastError()) != hipSuccess) return hip_fail("norm kernel launch", e);
                 if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
             }
-            {
+            if (c->refold) {
+                // the reduced gradient was not stored: fold every bucket again, now scaled by the coefficient
+                std::vector<uint32_t> ids(c->lay.buckets.size());
+                for (size_t i = 0; i < ids.size(); ++i) ids[i] = uint32_t(i);
+                rc = launch_buckets(c, ids.data(), ids.size(),
+                                    [&](size_t i) { return c->step_views.data() + i * W; }, s0, /*update=*/true);
+                if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+            } else {
                 ProfScope ps(c, SHADOW_K_ADAMW, s0);
                 if (ps.rc != SHADOW_OK) { c->poisoned = true; return ps.rc; }
                 const uint64_t nvec = c->lay.arena_numel >> 2;      // the arena is a multiple of 64 elements

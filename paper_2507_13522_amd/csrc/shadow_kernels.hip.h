@@ -216,9 +216,12 @@ __device__ __forceinline__ void adamw4(float* p, float* m, float* v, uint64_t ve
 // ---- kernel: fold + AdamW in one pass (clipping off) ---------------------------------
 // p, m, v are the arenas.  Within its bucket, thread i < n/4 owns elements 4i..4i+3 and
 // thread n/4 owns the (n mod 4) tail elements.
+// coef == nullptr: clipping off.  Otherwise the reduced gradient is multiplied by *coef first
+// (second fold of an iteration whose reduced gradient was not stored).
 template <bool BF16, int W>
 __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* __restrict__ p, float* __restrict__ m,
-                                                          float* __restrict__ v, WdMap map, StepScalars s)
+                                                          float* __restrict__ v, const float* __restrict__ coef, WdMap map,
+                                                          StepScalars s)
 {
     const uint32_t k = bucket_of_block(fb, blockIdx.x);
     const void* const* vp = fb.ptr + k * fb.w;
@@ -226,11 +229,13 @@ __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* _
     const uint64_t nvec = n >> 2;
     const uint64_t vec = uint64_t(blockIdx.x - fb.first_block[k]) * blockDim.x + threadIdx.x;
     if (vec < nvec) {
-        const f32x4 r = fold4<BF16, W>(vp, fb.w, vec, s);
+        f32x4 r = fold4<BF16, W>(vp, fb.w, vec, s);
+        if (coef) r = r * (*coef);
         adamw4(p + off, m + off, v + off, vec, off + (vec << 2), r, map, s);
     } else if (vec == nvec) {
         for (uint64_t e = nvec << 2; e < n; ++e) {
             float g = fold1<BF16>(vp, fb.w, e, s);
+            if (coef) g = g * (*coef);
             float pp = p[off + e], mm = m[off + e], vv = v[off + e];
             adamw_elem(pp, mm, vv, g, decay_factor_of(map, off + e, s.decay), s);
             p[off + e] = pp; m[off + e] = mm; v[off + e] = vv;
@@ -239,38 +244,64 @@ __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* _
 }
 
 // ---- kernel: fold + sum of squares, reduced gradient stored (clipping on) -------------
-// r is the scratch arena.  Every wave writes the sum of its lanes' squares to its own slot,
-// partial[slot_base of the bucket + wave index within the bucket]: no barrier, fixed order.
+// With few or narrow views a lane that owns only 4 elements moves too few bytes per wave
+// launched (W = 1 bf16: 8 bytes), so the lane owns kVpl groups of 4 elements, blockDim apart
+// (every load instruction of a wave still covers one contiguous run), chosen so that a lane
+// reads at least 64 bytes.
+template <bool BF16, int W>
+constexpr int fold_vpl()
+{
+    if (W <= 0) return 1;
+    const int bytes = 4 * (BF16 ? 2 : 4) * W;
+    const int v = 64 / bytes;
+    return v < 1 ? 1 : (v > 8 ? 8 : v);
+}
+
+// r == nullptr: the reduced gradient is not stored (it will be folded again for the update).
+// Every wave writes the sum of its lanes' squares to its own slot, partial[slot_base of the
+// bucket + wave index within the bucket]: no barrier, fixed order.
 template <bool BF16, int W>
 __global__ __launch_bounds__(kMaxBlock) void k_fold_sumsq(FoldBatch fb, float* __restrict__ r, double* __restrict__ partial,
                                                           StepScalars s)
 {
+    constexpr int kVpl = fold_vpl<BF16, W>();
     const uint32_t k = bucket_of_block(fb, blockIdx.x);
     const void* const* vp = fb.ptr + k * fb.w;
     const uint64_t n = fb.numel[k];
-    float* r_out = r + fb.arena_off[k];
+    float* r_out = r ? r + fb.arena_off[k] : nullptr;
     const uint64_t nvec = n >> 2;
-    const uint64_t vec = uint64_t(blockIdx.x - fb.first_block[k]) * blockDim.x + threadIdx.x;
-    double acc = 0.0;
-    if (vec < nvec) {
-        const f32x4 rr = fold4<BF16, W>(vp, fb.w, vec, s);
-        store_once(reinterpret_cast<f32x4*>(r_out) + vec, rr);
+    const uint32_t local_block = blockIdx.x - fb.first_block[k];
+    const uint64_t base = uint64_t(local_block) * blockDim.x * kVpl + threadIdx.x;
+    f32x4 rr[kVpl];
 #pragma unroll
-        for (int j = 0; j < kVec; ++j) {
-            const double d = double(rr[j]);
-            acc = fma(d, d, acc);        // d*d is exact in double, so this equals acc + d*d
-        }
-    } else if (vec == nvec) {
-        for (uint64_t e = nvec << 2; e < n; ++e) {
-            const float g = fold1<BF16>(vp, fb.w, e, s);
-            r_out[e] = g;
-            const double d = double(g);
-            acc = fma(d, d, acc);
+    for (int j = 0; j < kVpl; ++j) {
+        const uint64_t vec = base + uint64_t(j) * blockDim.x;
+        if (vec < nvec) rr[j] = fold4<BF16, W>(vp, fb.w, vec, s);
+    }
+    double acc = 0.0;
+#pragma unroll
+    for (int j = 0; j < kVpl; ++j) {
+        const uint64_t vec = base + uint64_t(j) * blockDim.x;
+        if (vec < nvec) {
+            if (r_out) store_once(reinterpret_cast<f32x4*>(r_out) + vec, rr[j]);
+#pragma unroll
+            for (int q = 0; q < kVec; ++q) {
+                const double d = double(rr[j][q]);
+                acc = fma(d, d, acc);        // d*d is exact in double, so this equals acc + d*d
+            }
+        } else if (vec == nvec) {
+            for (uint64_t e = nvec << 2; e < n; ++e) {
+                const float g = fold1<BF16>(vp, fb.w, e, s);
+                if (r_out) r_out[e] = g;
+                const double d = double(g);
+                acc = fma(d, d, acc);
+            }
         }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
-    if ((threadIdx.x & 63) == 0) partial[fb.slot_base[k] + (vec >> 6)] = acc;
+    if ((threadIdx.x & 63) == 0)
+        partial[fb.slot_base[k] + uint64_t(local_block) * (blockDim.x >> 6) + (threadIdx.x >> 6)] = acc;
 }
 
 // ---- block-wide sum of doubles in a fixed order ----------------------------------------

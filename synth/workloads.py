@@ -109,6 +109,12 @@ def _llama7b() -> Workload:
                     grad_sigma=1e-3, steps=5, max_grad_norm=1.0, bucket_cap_bytes=50 * MIB)
 
 
+def _llama7b_w1() -> Workload:
+    """The paper's own situation: the shadow receives ONE already-reduced gradient per bucket (W = 1)."""
+    return Workload("llama7b_w1", _llama7b_tensors(), num_workers=1, grad_dtype="bf16", grad_dist="normal",
+                    grad_sigma=3.5e-4, steps=3, max_grad_norm=1.0, bucket_cap_bytes=50 * MIB)
+
+
 def _ragged7b() -> Workload:
     """7B tensor list plus 1,709 small ragged tensors at seeded positions.
 
@@ -156,6 +162,7 @@ WORKLOADS = {
     "gpt2s": _gpt2_small,
     "gpt1p3b": _gpt_1p3b,
     "llama7b": _llama7b,
+    "llama7b_w1": _llama7b_w1,
     "ragged7b": _ragged7b,
 }
 

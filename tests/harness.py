@@ -149,7 +149,7 @@ class GpuShadow:
 
     def __init__(self, wl: synth.Workload, inputs: Inputs, num_streams: int = 2, mean: bool = True,
                  torch_streams: bool = False, resident_grads: bool = True, init_from=None, start_step: int = 0,
-                 advised_placement: bool = True, batch_bytes: int = 0):
+                 advised_placement: bool = True, batch_bytes: int = 0, refold: bool = False):
         assert torch.cuda.is_available()
         self.wl, self.inputs = wl, inputs
         self.dev = torch.device("cuda:0")
@@ -166,11 +166,11 @@ class GpuShadow:
         # placement follows the library's advice: the arenas are carved from ONE allocation, a power-of-two
         # stride apart; the gradient views sit in a bucket-major staging buffer
         stride = L.arena_stride() if advised_placement else (A * 4 + 255) // 256 * 256
-        narr = 4 if clip else 3
+        narr = 4 if (clip and not refold) else 3          # re-fold mode: clipping without a scratch arena
         self._state = torch.empty((narr - 1) * stride + A * 4, dtype=torch.uint8, device=self.dev)
         arenas = [self._state[k * stride:k * stride + A * 4].view(torch.float32) for k in range(narr)]
         self.p, self.m, self.v = arenas[:3]
-        self.r = arenas[3] if clip else None
+        self.r = arenas[3] if narr == 4 else None
         self.m.zero_()
         self.v.zero_()
         if init_from is None:

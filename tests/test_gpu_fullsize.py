@@ -55,7 +55,7 @@ def pick_buckets(lay: oracle.Layout, budget: int):
 
 
 def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resident: bool, num_streams: int = 2,
-                 batch_bytes: int = 0):
+                 batch_bytes: int = 0, refold: bool = False):
     wl = synth.get_workload(name)
     say(f"case fullsize {name}: P={wl.num_params} W={wl.num_workers} steps={steps}")
     t_start = time.time()
@@ -69,7 +69,7 @@ def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resi
     clip = wl.max_grad_norm > 0
     W = wl.num_workers
 
-    g = GpuShadow(wl, inp, num_streams=num_streams, resident_grads=resident, batch_bytes=batch_bytes)
+    g = GpuShadow(wl, inp, num_streams=num_streams, resident_grads=resident, batch_bytes=batch_bytes, refold=refold)
     B = len(g.buckets)
     ring = None
     if not resident:
@@ -176,6 +176,12 @@ def test_llama7b_full():
 
 def test_llama7b_full_one_launch_per_bucket():
     run_fullsize("llama7b", steps=2, bucket_budget=60_000_000, n_scatter=500_000, resident=True, num_streams=2, batch_bytes=0)
+
+
+def test_llama7b_single_reduced_gradient_full():
+    """W = 1 (the shadow is handed the already-reduced gradient, as in the paper), clipping without a scratch arena."""
+    run_fullsize("llama7b_w1", steps=3, bucket_budget=60_000_000, n_scatter=500_000, resident=True, num_streams=BENCH_STREAMS,
+                 batch_bytes=BENCH_BATCH_BYTES, refold=True)
 
 
 def test_ragged7b_full():

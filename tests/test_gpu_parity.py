@@ -29,12 +29,13 @@ def custom(name, sizes_flags, W, dtype, clip=0.0, cap=1 << 16, steps=3, dist="no
 
 
 def check_against_oracle(wl, steps=None, num_streams=2, mean=True, every_step=True, exact=True, torch_streams=False,
-                         batch_bytes=0):
+                         batch_bytes=0, refold=False):
     """Run both sides on the same inputs and compare param, m, v of every bucket."""
     steps = steps or wl.steps
     inp = Inputs(wl)
     assert_layouts_agree(oracle_layout(wl), lib_layout(wl))
-    g = GpuShadow(wl, inp, num_streams=num_streams, mean=mean, torch_streams=torch_streams, batch_bytes=batch_bytes)
+    g = GpuShadow(wl, inp, num_streams=num_streams, mean=mean, torch_streams=torch_streams, batch_bytes=batch_bytes,
+                  refold=refold)
     worst = {}
 
     def on_step(t, orc):
@@ -96,6 +97,19 @@ def test_worker_counts(W, dtype, clip):
     say("case W", W, dtype, clip)
     wl = custom("wsweep", [(20011, True), (4099, False), (9000, True), (17, False)], W, dtype, clip=clip, cap=30_000, steps=2)
     check_against_oracle(wl, num_streams=2)
+
+
+@pytest.mark.parametrize("W,dtype", [(1, "bf16"), (1, "f32"), (3, "bf16"), (8, "bf16"), (64, "f32")])
+@pytest.mark.parametrize("batch_bytes", [0, 1 << 62])
+def test_clip_without_scratch_folds_twice(W, dtype, batch_bytes):
+    """Clipping with no scratch arena (W = 1 is the paper's case of one already-reduced gradient): the views are
+    folded once for the norm and once more for the update; same bits as the oracle and as the stored path."""
+    say("case refold", W, dtype, batch_bytes)
+    wl = custom("refold", RAGGED, W, dtype, clip=0.01, cap=200_000, steps=4, random_arrival=True)
+    check_against_oracle(wl, num_streams=2, batch_bytes=batch_bytes, refold=True)
+    many = custom("refold-many", [(int(n), bool(n % 3)) for n in np.random.default_rng(W).integers(1, 2000, 90)], W, dtype,
+                  clip=0.003, cap=3000, steps=2)
+    check_against_oracle(many, num_streams=3, batch_bytes=batch_bytes, refold=True)
 
 
 def test_sum_reduce_and_student_t():

@@ -83,7 +83,7 @@ def test_init_validates_before_touching_the_gpu():
                 grad_dtype=sh.GRAD_BF16, reduce_op=sh.REDUCE_MEAN, num_streams=1)
     bad = [dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0), dict(lr=-1.0), dict(num_workers=0), dict(num_workers=65),
            dict(grad_dtype=7), dict(grad_dtype=sh.GRAD_F32), dict(reduce_op=3), dict(num_streams=0), dict(num_streams=17),
-           dict(weight_decay=-1.0), dict(max_grad_norm=1.0)]          # clipping on but no scratch arena
+           dict(weight_decay=-1.0)]
     for kw in bad:
         hp = sh.HParams(**{**good, **kw})
         with pytest.raises(sh.ShadowError) as e:

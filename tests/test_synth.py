@@ -6,7 +6,8 @@ import synth
 
 
 def test_workload_sizes():
-    want = {"tiny": 1_048_576, "gpt2s": 124_439_808, "gpt1p3b": 1_315_723_264, "llama7b": 6_738_415_616}
+    want = {"tiny": 1_048_576, "gpt2s": 124_439_808, "gpt1p3b": 1_315_723_264, "llama7b": 6_738_415_616,
+            "llama7b_w1": 6_738_415_616}
     for k, p in want.items():
         assert synth.get_workload(k).num_params == p
     w = synth.get_workload("ragged7b")
