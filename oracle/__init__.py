@@ -8,8 +8,12 @@ from .shadow import (  # noqa: F401
     HParams,
     OracleShadow,
     SumSq,
+    adam_f32,
+    adam_f64,
     adamw_f32,
     adamw_f64,
+    sgd_f32,
+    sgd_f64,
     clip_coef,
     fold,
     get_threads,

@@ -60,9 +60,14 @@ def lib() -> C.CDLL:
                                        + [C.c_uint64, C.c_int, C.c_float])
         L.oracle_adamw_f64.argtypes = ([C.c_void_p] * 4 + [C.c_uint64, C.c_int] + [C.c_double] * 5
                                        + [C.c_uint64, C.c_int, C.c_double])
+        L.oracle_adam_f32.argtypes = L.oracle_adamw_f32.argtypes
+        L.oracle_adam_f64.argtypes = L.oracle_adamw_f64.argtypes
+        L.oracle_sgd_f32.argtypes = [C.c_void_p] * 3 + [C.c_uint64, C.c_int] + [C.c_float] * 3 + [C.c_int, C.c_float]
+        L.oracle_sgd_f64.argtypes = [C.c_void_p] * 3 + [C.c_uint64, C.c_int] + [C.c_double] * 3 + [C.c_int, C.c_double]
         for name in ("oracle_set_threads", "oracle_widen_bf16", "oracle_sumsq_accumulate",
                      "oracle_sumsq_accumulate_f64", "oracle_sumsq_accumulate_weighted",
-                     "oracle_step_scalars", "oracle_adamw_f32", "oracle_adamw_f64"):
+                     "oracle_step_scalars", "oracle_adamw_f32", "oracle_adamw_f64", "oracle_adam_f32",
+                     "oracle_adam_f64", "oracle_sgd_f32", "oracle_sgd_f64"):
             getattr(L, name).restype = None
     return _lib
 
@@ -179,6 +184,7 @@ class HParams:
     weight_decay: float = 0.01
     max_grad_norm: float = 0.0      # <= 0: clipping off
     mean: bool = True               # average (True) or sum (False) over workers
+    optimizer: str = "adamw"        # "adamw" | "adam" (L2 penalty in the gradient) | "sgd" (momentum = beta1)
 
     def f32(self, name: str) -> float:
         """The hyper-parameter as the float the method receives, widened."""
@@ -200,6 +206,46 @@ def adamw_f32(p, m, v, r, wd_flag: bool, hp: HParams, t: int, c=None) -> None:
     lib().oracle_adamw_f32(_ptr(p), _ptr(m), _ptr(v), _ptr(r), n, int(bool(wd_flag)),
                            hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, int(t),
                            int(c is not None), C.c_float(0.0 if c is None else float(c)))
+
+
+def adam_f32(p, m, v, r, wd_flag: bool, hp: HParams, t: int, c=None) -> None:
+    n = p.size
+    for a in (p, m, v, r):
+        _chk(a, np.float32)
+        assert a.size == n
+    lib().oracle_adam_f32(_ptr(p), _ptr(m), _ptr(v), _ptr(r), n, int(bool(wd_flag)),
+                          hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, int(t),
+                          int(c is not None), C.c_float(0.0 if c is None else float(c)))
+
+
+def adam_f64(p, m, v, r, wd_flag: bool, hp: HParams, t: int, c=None) -> None:
+    n = p.size
+    for a in (p, m, v, r):
+        _chk(a, np.float64)
+        assert a.size == n
+    lib().oracle_adam_f64(_ptr(p), _ptr(m), _ptr(v), _ptr(r), n, int(bool(wd_flag)),
+                          hp.f32("lr"), hp.f32("beta1"), hp.f32("beta2"), hp.f32("eps"),
+                          hp.f32("weight_decay"), int(t), int(c is not None),
+                          C.c_double(0.0 if c is None else float(c)))
+
+
+def sgd_f32(p, b, r, wd_flag: bool, hp: HParams, c=None) -> None:
+    """Momentum SGD; the momentum coefficient is hp.beta1, the buffer b lives where Adam keeps m."""
+    n = p.size
+    for a in (p, b, r):
+        _chk(a, np.float32)
+        assert a.size == n
+    lib().oracle_sgd_f32(_ptr(p), _ptr(b), _ptr(r), n, int(bool(wd_flag)), hp.lr, hp.beta1, hp.weight_decay,
+                         int(c is not None), C.c_float(0.0 if c is None else float(c)))
+
+
+def sgd_f64(p, b, r, wd_flag: bool, hp: HParams, c=None) -> None:
+    n = p.size
+    for a in (p, b, r):
+        _chk(a, np.float64)
+        assert a.size == n
+    lib().oracle_sgd_f64(_ptr(p), _ptr(b), _ptr(r), n, int(bool(wd_flag)), hp.f32("lr"), hp.f32("beta1"),
+                         hp.f32("weight_decay"), int(c is not None), C.c_double(0.0 if c is None else float(c)))
 
 
 def adamw_f64(p, m, v, r, wd_flag: bool, hp: HParams, t: int, c=None) -> None:
@@ -239,10 +285,14 @@ class OracleShadow:
 
     def update_bucket(self, b: int, r: np.ndarray, t: int, c) -> None:
         """Optimizer step on bucket b's tensors, each through its offset view."""
-        fn = adamw_f32 if self.precision == "f32" else adamw_f64
+        f32 = self.precision == "f32"
         for s in self.layout.buckets[b].segments:
             sl = slice(s.offset, s.offset + s.numel)
-            fn(self.p[b][sl], self.m[b][sl], self.v[b][sl], r[sl], s.weight_decay, self.hp, t, c)
+            if self.hp.optimizer == "sgd":
+                (sgd_f32 if f32 else sgd_f64)(self.p[b][sl], self.m[b][sl], r[sl], s.weight_decay, self.hp, c)
+            else:
+                fn = {"adamw": (adamw_f32, adamw_f64), "adam": (adam_f32, adam_f64)}[self.hp.optimizer][0 if f32 else 1]
+                fn(self.p[b][sl], self.m[b][sl], self.v[b][sl], r[sl], s.weight_decay, self.hp, t, c)
 
     def step(self, grads: Dict[int, Sequence[np.ndarray]]) -> None:
         """One iteration: every bucket's W views must be present exactly once."""

@@ -231,3 +231,82 @@ void oracle_adamw_f64(double *p, double *m, double *v, const double *r, uint64_t
         v[i] = vi;
     }
 }
+
+/* ---- other functional optimizers (section 4.2.4 names SGD, Adam and AdamW) --
+ * Adam (Kingma & Ba) with the classic L2 penalty: the decay term joins the
+ * gradient, g' = g + wd*p (on tensors with the flag), and then the moments and
+ * the bias-corrected step are those of AdamW without its decay multiply.      */
+void oracle_adam_f32(float *p, float *m, float *v, const float *r, uint64_t n, int wd_flag,
+                     float lr, float beta1, float beta2, float eps, float wd, uint64_t t,
+                     int clip, float c)
+{
+    float s[5];
+    oracle_step_scalars(lr, beta1, beta2, wd, t, s);
+    const float omb1 = s[1], omb2 = s[2], step_size = s[3], isq = s[4];
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i) {
+        float g = r[i];
+        if (clip) g = g * c;
+        float pi = p[i];
+        if (wd_flag) g = g + wd * pi;
+        float mi = beta1 * m[i] + omb1 * g;
+        float vi = beta2 * v[i] + (omb2 * g) * g;
+        float denom = sqrtf(vi) * isq + eps;
+        pi = pi - step_size * (mi / denom);
+        p[i] = pi;
+        m[i] = mi;
+        v[i] = vi;
+    }
+}
+
+void oracle_adam_f64(double *p, double *m, double *v, const double *r, uint64_t n, int wd_flag,
+                     double lr, double beta1, double beta2, double eps, double wd, uint64_t t,
+                     int clip, double c)
+{
+    const double bc1 = 1.0 - pow(beta1, (double)t);
+    const double bc2 = 1.0 - pow(beta2, (double)t);
+    for (uint64_t i = 0; i < n; ++i) {
+        double g = clip ? r[i] * c : r[i];
+        double pi = p[i];
+        if (wd_flag) g = g + wd * pi;
+        double mi = beta1 * m[i] + (1.0 - beta1) * g;
+        double vi = beta2 * v[i] + (1.0 - beta2) * g * g;
+        pi = pi - lr * (mi / bc1) / (sqrt(vi / bc2) + eps);
+        p[i] = pi;
+        m[i] = mi;
+        v[i] = vi;
+    }
+}
+
+/* SGD with momentum mu (no dampening, no Nesterov), L2 penalty in the gradient:
+ *   g' = g + wd*p ; b = mu*b + g' ; p = p - lr*b.   b starts at zero, so the
+ *   first step is b = g'.  mu = 0 is plain SGD.                               */
+void oracle_sgd_f32(float *p, float *b, const float *r, uint64_t n, int wd_flag,
+                    float lr, float mu, float wd, int clip, float c)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i) {
+        float g = r[i];
+        if (clip) g = g * c;
+        float pi = p[i];
+        if (wd_flag) g = g + wd * pi;
+        float bi = mu * b[i] + g;
+        pi = pi - lr * bi;
+        p[i] = pi;
+        b[i] = bi;
+    }
+}
+
+void oracle_sgd_f64(double *p, double *b, const double *r, uint64_t n, int wd_flag,
+                    double lr, double mu, double wd, int clip, double c)
+{
+    for (uint64_t i = 0; i < n; ++i) {
+        double g = clip ? r[i] * c : r[i];
+        double pi = p[i];
+        if (wd_flag) g = g + wd * pi;
+        double bi = mu * b[i] + g;
+        pi = pi - lr * bi;
+        p[i] = pi;
+        b[i] = bi;
+    }
+}

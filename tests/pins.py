@@ -414,6 +414,155 @@ def pin_step_scalars():
         assert abs(isq * isq * (1 - b2 ** t) - 1) <= Fraction(1, 2 ** 21), t
 
 
+# --------------------------------------------------------------------------- Adam (L2 in the gradient) and SGD
+def pin_adam_coupled_decay():
+    # without decay Adam and AdamW are the same arithmetic, bit for bit
+    hp0 = _hp(weight_decay=0.0)
+    n, T = 500, 5
+    rng = _rng(21)
+    p0 = (rng.standard_normal(n) * 0.02).astype(F32)
+    gs = [(rng.standard_normal(n) * 1e-3).astype(F32) for _ in range(T)]
+    a = [p0.copy(), np.zeros(n, F32), np.zeros(n, F32)]
+    b = [p0.copy(), np.zeros(n, F32), np.zeros(n, F32)]
+    for t, g in enumerate(gs, 1):
+        oracle.adamw_f32(*a, g, True, hp0, t)
+        oracle.adam_f32(*b, g, True, hp0, t)
+    for x, y in zip(a, b):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    # with decay the penalty enters the gradient: zero gradient, first step: g' = wd*p, dp = -lr*g'/(|g'|+eps)
+    hp = _hp(weight_decay=0.1)
+    lr, eps, wd = hp.f32("lr"), hp.f32("eps"), hp.f32("weight_decay")
+    pd, md, vd = p0.astype(np.float64), np.zeros(n), np.zeros(n)
+    oracle.adam_f64(pd, md, vd, np.zeros(n), True, hp, 1)
+    gp = wd * p0.astype(np.float64)
+    assert np.allclose(pd - p0, -lr * gp / (np.abs(gp) + eps), rtol=1e-10, atol=1e-18)
+    assert np.allclose(md, (1 - hp.f32("beta1")) * gp, rtol=1e-13) and np.allclose(vd, (1 - hp.f32("beta2")) * gp * gp, rtol=1e-13)
+    # masked tensor: no penalty, zero gradient leaves everything unchanged
+    q = [p0.copy(), np.zeros(n, F32), np.zeros(n, F32)]
+    oracle.adam_f32(*q, np.zeros(n, F32), False, hp, 1)
+    assert np.array_equal(q[0], p0) and not q[1].any() and not q[2].any()
+    # float order: g' = g + wd*p (one multiply, one add)
+    g = gs[0]
+    q = [p0.copy(), np.zeros(n, F32), np.zeros(n, F32)]
+    oracle.adam_f32(*q, g, True, hp, 1)
+    g2 = g + F32(wd) * p0
+    assert np.array_equal(q[1], F32(1.0 - hp.f32("beta1")) * g2)
+    # library: torch.optim.Adam with weight_decay, double
+    tp = torch.nn.Parameter(torch.tensor(p0, dtype=torch.float64))
+    opt = torch.optim.Adam([tp], lr=lr, betas=(hp.f32("beta1"), hp.f32("beta2")), eps=eps, weight_decay=wd, foreach=False)
+    pd, md, vd = p0.astype(np.float64), np.zeros(n), np.zeros(n)
+    for t, g in enumerate(gs, 1):
+        tp.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        oracle.adam_f64(pd, md, vd, g.astype(np.float64), True, hp, t)
+    assert np.allclose(pd, tp.detach().numpy(), rtol=1e-11, atol=1e-16)
+    assert np.allclose(md, opt.state[tp]["exp_avg"].numpy(), rtol=1e-11, atol=1e-18)
+    assert np.allclose(vd, opt.state[tp]["exp_avg_sq"].numpy(), rtol=1e-11, atol=1e-24)
+    # float variant near the double one
+    q = [p0.copy(), np.zeros(n, F32), np.zeros(n, F32)]
+    for t, g in enumerate(gs, 1):
+        oracle.adam_f32(*q, g, True, hp, t)
+    assert np.allclose(q[0], pd, rtol=0, atol=T * 4e-9 + 2e-9)
+
+
+def pin_sgd_momentum():
+    hp = HParams(lr=0.1, beta1=0.9, weight_decay=0.0, optimizer="sgd")
+    lr, mu = hp.f32("lr"), hp.f32("beta1")
+    g32 = np.array([1e-3, -2.5e-4, 0.7, -3.0], F32)
+    gd = g32.astype(np.float64)
+    T = 9
+    pd, bd = np.zeros(4), np.zeros(4)
+    p, b = np.zeros(4, F32), np.zeros(4, F32)
+    total = np.zeros(4)
+    for t in range(1, T + 1):
+        oracle.sgd_f64(pd, bd, gd, False, hp)
+        oracle.sgd_f32(p, b, g32, False, hp)
+        want_b = gd * (1 - mu ** t) / (1 - mu)            # geometric series: b_t = g (1 + mu + ... + mu^(t-1))
+        total += want_b
+        assert np.allclose(bd, want_b, rtol=1e-12) and np.allclose(pd, -lr * total, rtol=1e-12)
+        assert np.allclose(b, bd, rtol=1e-5) and np.allclose(p, pd, rtol=1e-5)
+    # first step: the buffer is the gradient itself
+    p, b = np.ones(4, F32), np.zeros(4, F32)
+    oracle.sgd_f32(p, b, g32, False, hp)
+    assert np.array_equal(b, g32) and np.array_equal(p, np.ones(4, F32) - F32(0.1) * g32)
+    # zero gradient: the buffer decays geometrically and keeps moving p
+    b0 = g32.copy()
+    p, b = np.zeros(4, F32), b0.copy()
+    z = np.zeros(4, F32)
+    bb, pp = b0.copy(), np.zeros(4, F32)
+    for t in range(6):
+        oracle.sgd_f32(p, b, z, False, hp)
+        bb = F32(0.9) * bb
+        pp = pp - F32(0.1) * bb
+        assert np.array_equal(b, bb) and np.array_equal(p, pp)
+    # no momentum: plain gradient descent
+    hp_plain = HParams(lr=0.1, beta1=0.0, weight_decay=0.0, optimizer="sgd")
+    p, b = np.ones(4, F32), np.zeros(4, F32)
+    for t in range(3):
+        oracle.sgd_f32(p, b, g32, False, hp_plain)
+    want = np.ones(4, F32)
+    for t in range(3):
+        want = want - F32(0.1) * g32
+    assert np.array_equal(p, want)
+    # L2 penalty and its mask; clipping scales the gradient before the penalty is added
+    hp_wd = HParams(lr=0.1, beta1=0.9, weight_decay=0.5, optimizer="sgd")
+    p, b = np.full(4, 2.0, F32), np.zeros(4, F32)
+    oracle.sgd_f32(p, b, z, True, hp_wd)
+    assert np.array_equal(b, np.full(4, 1.0, F32)) and np.array_equal(p, np.full(4, 2.0, F32) - F32(0.1) * F32(1.0))
+    p, b = np.full(4, 2.0, F32), np.zeros(4, F32)
+    oracle.sgd_f32(p, b, z, False, hp_wd)
+    assert np.array_equal(p, np.full(4, 2.0, F32)) and not b.any()
+    p, b = np.full(4, 2.0, F32), np.zeros(4, F32)
+    oracle.sgd_f32(p, b, np.full(4, 4.0, F32), True, hp_wd, c=F32(0.25))
+    assert np.array_equal(b, np.full(4, 2.0, F32))            # 4*0.25 + 0.5*2
+    # library: torch.optim.SGD, double
+    rng = _rng(22)
+    n, T = 300, 6
+    p0 = (rng.standard_normal(n) * 0.02).astype(F32)
+    gs = [(rng.standard_normal(n) * 1e-3).astype(F32) for _ in range(T)]
+    hp_t = HParams(lr=0.05, beta1=0.9, weight_decay=0.01, optimizer="sgd")
+    tp = torch.nn.Parameter(torch.tensor(p0, dtype=torch.float64))
+    opt = torch.optim.SGD([tp], lr=hp_t.f32("lr"), momentum=hp_t.f32("beta1"), weight_decay=hp_t.f32("weight_decay"), foreach=False)
+    pd, bd = p0.astype(np.float64), np.zeros(n)
+    p, b = p0.copy(), np.zeros(n, F32)
+    for g in gs:
+        tp.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        oracle.sgd_f64(pd, bd, g.astype(np.float64), True, hp_t)
+        oracle.sgd_f32(p, b, g, True, hp_t)
+    assert np.allclose(pd, tp.detach().numpy(), rtol=1e-13, atol=1e-18)
+    assert np.allclose(bd, opt.state[tp]["momentum_buffer"].numpy(), rtol=1e-13, atol=1e-20)
+    assert np.allclose(p, pd, rtol=0, atol=T * 4e-9) and np.abs(b - bd).max() <= 8 * T * 2 ** -24 * np.abs(bd).max()
+
+
+def pin_driver_dispatches_optimizers():
+    """OracleShadow routes every tensor through the optimizer named in the hyper-parameters."""
+    tensors = [(40, True), (9, False), (70, True)]
+    lay = oracle.build_layout(tensors, 4, 200)
+    rng = _rng(23)
+    p0 = [(rng.standard_normal(b.numel) * 0.02).astype(F32) for b in lay.buckets]
+    g = {bi: [(rng.standard_normal(b.numel) * 1e-3).astype(F32) for _ in range(2)] for bi, b in enumerate(lay.buckets)}
+    for name in ("adamw", "adam", "sgd"):
+        hp = HParams(lr=1e-2, weight_decay=0.1, optimizer=name, max_grad_norm=1e-3)
+        orc = oracle.OracleShadow(lay, hp, p0)
+        orc.step(g)
+        c = orc.last_coef
+        for bi, b in enumerate(lay.buckets):
+            r = oracle.fold(g[bi])
+            for sgm in b.segments:
+                sl = slice(sgm.offset, sgm.offset + sgm.numel)
+                q = [p0[bi][sl].copy(), np.zeros(sgm.numel, F32), np.zeros(sgm.numel, F32)]
+                if name == "sgd":
+                    oracle.sgd_f32(q[0], q[1], r[sl].copy(), sgm.weight_decay, hp, c)
+                else:
+                    getattr(oracle, name + "_f32")(*q, r[sl].copy(), sgm.weight_decay, hp, 1, c)
+                assert np.array_equal(orc.p[bi][sl], q[0]) and np.array_equal(orc.m[bi][sl], q[1])
+    a = oracle.OracleShadow(lay, HParams(lr=1e-2, weight_decay=0.1, optimizer="adamw"), p0)
+    b = oracle.OracleShadow(lay, HParams(lr=1e-2, weight_decay=0.1, optimizer="adam"), p0)
+    a.step(g); b.step(g)
+    assert not np.array_equal(a.p[0], b.p[0])         # decoupled and coupled decay differ
+
+
 ALL_PINS = [
     pin_widen_bf16_exhaustive,
     pin_fold_identity_and_equal_workers,
@@ -429,4 +578,7 @@ ALL_PINS = [
     pin_f32_vs_torch_f32,
     pin_layout,
     pin_step_scalars,
+    pin_adam_coupled_decay,
+    pin_sgd_momentum,
+    pin_driver_dispatches_optimizers,
 ]

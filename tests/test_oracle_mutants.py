@@ -36,6 +36,14 @@ MUTANTS = [
     ("f64_no_decay", "if (wd_flag) pi = pi * (1.0 - lr * wd);", ""),
     ("f64_mhat_uses_bc2", "double mhat = mi / bc1;", "double mhat = mi / bc2;"),
     ("f64_clip_not_applied", "double g = clip ? r[i] * c : r[i];", "double g = r[i];"),
+    ("adam_decay_decoupled_instead", "if (wd_flag) g = g + wd * pi;\n        float mi = beta1 * m[i] + omb1 * g;", "if (wd_flag) pi = pi * (1.0f - lr * wd);\n        float mi = beta1 * m[i] + omb1 * g;"),
+    ("adam_penalty_sign", "if (wd_flag) g = g + wd * pi;\n        float mi", "if (wd_flag) g = g - wd * pi;\n        float mi"),
+    ("adam_f64_penalty_dropped", "if (wd_flag) g = g + wd * pi;\n        double mi", "double mi"),
+    ("sgd_momentum_on_gradient", "float bi = mu * b[i] + g;", "float bi = b[i] + mu * g;"),
+    ("sgd_dampening", "float bi = mu * b[i] + g;", "float bi = mu * b[i] + (1.0f - mu) * g;"),
+    ("sgd_step_uses_gradient", "pi = pi - lr * bi;\n        p[i] = pi;\n        b[i] = bi;\n    }\n}\n\nvoid oracle_sgd_f64", "pi = pi - lr * g;\n        p[i] = pi;\n        b[i] = bi;\n    }\n}\n\nvoid oracle_sgd_f64"),
+    ("sgd_penalty_ignores_mask", "if (wd_flag) g = g + wd * pi;\n        float bi", "g = g + wd * pi;\n        float bi"),
+    ("sgd_clip_after_penalty", "if (clip) g = g * c;\n        float pi = p[i];\n        if (wd_flag) g = g + wd * pi;\n        float bi", "float pi = p[i];\n        if (wd_flag) g = g + wd * pi;\n        if (clip) g = g * c;\n        float bi"),
     ("scalars_decay_wrong", "out[0] = (float)(1.0 - (double)lr * (double)wd);", "out[0] = (float)(1.0 - (double)wd);"),
 ]
 
