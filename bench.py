@@ -49,17 +49,18 @@ def measured_traffic(workload: str, kernel: str):
 KERNEL_NAMES = {0: "k_fold_adamw", 1: "k_fold_sumsq", 2: "k_norm_finalize", 3: "k_adamw"}
 
 
-def algorithmic_bytes_per_param(wl, refold: bool = False) -> dict:
+def algorithmic_bytes_per_param(wl, refold: bool = False, optimizer: str = "adamw") -> dict:
     """Bytes the method must move per parameter and step, by kernel (measurement)."""
     g = wl.grad_bytes * wl.num_workers
+    st = 16 if optimizer == "sgd" else 24        # state read + written: p, m (, v)
     if wl.max_grad_norm > 0 and refold:          # views folded twice, reduced gradient never stored
-        return {"k_fold_sumsq": g, "k_fold_adamw": g + 24, "total": 2 * g + 24}
+        return {"k_fold_sumsq": g, "k_fold_adamw": g + st, "total": 2 * g + st}
     if wl.max_grad_norm > 0:
-        return {"k_fold_sumsq": g + 4, "k_adamw": 4 + 24, "total": g + 32}
-    return {"k_fold_adamw": g + 24, "total": g + 24}
+        return {"k_fold_sumsq": g + 4, "k_adamw": 4 + st, "total": g + 8 + st}
+    return {"k_fold_adamw": g + st, "total": g + st}
 
 
-def cpu_baseline(wl, inputs, target_seconds: float = 15.0) -> dict:
+def cpu_baseline(wl, inputs, target_seconds: float = 15.0, optimizer: str = "adamw") -> dict:
     """Time the oracle, as it stands, on this machine's host cores over a bounded sample of the same workload."""
     import numpy as np
     import oracle
@@ -67,7 +68,7 @@ def cpu_baseline(wl, inputs, target_seconds: float = 15.0) -> dict:
 
     lay = oracle_layout(wl)
     starts = lay.logical_starts()
-    hp = oracle_hparams(wl)
+    hp = oracle_hparams(wl, optimizer=optimizer)
     threads = oracle.get_threads()
     # sample: buckets in id order until ~64M elements (bounded host memory), repeated until the time budget is used
     chosen, total = [], 0
@@ -100,7 +101,7 @@ def cpu_baseline(wl, inputs, target_seconds: float = 15.0) -> dict:
         done += total
     return {"value": done / t_used, "unit": "params/s", "cores": threads, "kind": "oracle",
             "sample": f"{len(chosen)} buckets ({total} params) of {wl.name}, {t} oracle iterations "
-                      f"(fold W={wl.num_workers} {wl.grad_dtype}, norm, AdamW), {t_used:.1f} s of CPU work, "
+                      f"(fold W={wl.num_workers} {wl.grad_dtype}, norm, {optimizer}), {t_used:.1f} s of CPU work, "
                       f"OpenMP threads={threads}, host cpus={os.cpu_count()}"}
 
 
@@ -116,6 +117,7 @@ def main() -> int:
                          "its own launch; default: the whole iteration in as few launches as the descriptor allows)")
     ap.add_argument("--refold", action="store_true",
                     help="clipping without a scratch arena: fold the views twice instead of storing the reduced gradient")
+    ap.add_argument("--optimizer", default="adamw", choices=["adamw", "adam", "sgd"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fold-block", type=int, default=0)
     ap.add_argument("--adamw-block", type=int, default=0)
@@ -145,7 +147,7 @@ def main() -> int:
 
     wl = synth.get_workload(args.workload)
     inputs = Inputs(wl, period=TILE_PERIOD)
-    g = GpuShadow(wl, inputs, num_streams=streams, batch_bytes=batch_bytes, refold=args.refold)
+    g = GpuShadow(wl, inputs, num_streams=streams, batch_bytes=batch_bytes, refold=args.refold, optimizer=args.optimizer)
     P = g.layout.num_params
     g.fill_grads(1)            # the same resident views serve every timed step (values do not affect timing)
     step = 0
@@ -173,7 +175,7 @@ def main() -> int:
     g.ctx.profile_enable(False)
 
     ms_per_step = 1e3 * elapsed / args.steps
-    bpp = algorithmic_bytes_per_param(wl, args.refold)
+    bpp = algorithmic_bytes_per_param(wl, args.refold, args.optimizer)
     kernels = {}
     for kind, name in KERNEL_NAMES.items():
         n, ms = g.ctx.profile_read(kind)
@@ -204,10 +206,10 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {P} fp32 params (+m, v) in {len(g.buckets)} buckets of <= "
                                f"{wl.bucket_cap_bytes >> 20} MiB, W={wl.num_workers} {wl.grad_dtype} gradient views per bucket, "
-                               f"AdamW" + (f" + global-norm clip at {wl.max_grad_norm}" if wl.max_grad_norm > 0 else ""),
+                               f"{args.optimizer}" + (f" + global-norm clip at {wl.max_grad_norm}" if wl.max_grad_norm > 0 else ""),
                    "num_params": P, "num_buckets": len(g.buckets), "num_workers": wl.num_workers,
                    "grad_dtype": wl.grad_dtype, "streams": streams,
-                   "batch_bytes": batch_bytes, "refold": bool(args.refold)},
+                   "batch_bytes": batch_bytes, "refold": bool(args.refold), "optimizer": args.optimizer},
         "hbm_GBps": total_gbs,
         "hbm_frac_of_peak": total_gbs / HBM_PEAK_GBS,
         "bytes_per_param": bpp["total"],
@@ -218,7 +220,7 @@ def main() -> int:
     }
     g.close()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, inputs)
+        out["cpu_baseline"] = cpu_baseline(wl, inputs, optimizer=args.optimizer)
     print(json.dumps(out))
     return 0
 

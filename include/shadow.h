@@ -46,6 +46,11 @@ typedef enum {
 
 enum { SHADOW_GRAD_F32 = 0, SHADOW_GRAD_BF16 = 1 };
 enum { SHADOW_REDUCE_MEAN = 0, SHADOW_REDUCE_SUM = 1 };
+/* Functional optimizers (section 4.2.4).  ADAMW: decoupled decay.  ADAM: the L2 penalty joins
+ * the gradient (g += weight_decay*p).  SGD: g += weight_decay*p; b = beta1*b + g; p -= lr*b, with
+ * beta1 as the momentum coefficient and b kept in the m arena; beta2, eps are ignored and the v
+ * arena must be NULL. */
+enum { SHADOW_OPT_ADAMW = 0, SHADOW_OPT_ADAM = 1, SHADOW_OPT_SGD = 2 };
 enum { SHADOW_MAX_WORKERS = 64, SHADOW_MAX_STREAMS = 16 };
 
 /* One model tensor.  Tensors are listed in MODEL order (first layer first). */
@@ -67,6 +72,7 @@ typedef struct {
     uint32_t grad_dtype;     /* SHADOW_GRAD_F32 or SHADOW_GRAD_BF16                        */
     uint32_t reduce_op;      /* SHADOW_REDUCE_MEAN (sum * float(1/W)) or SHADOW_REDUCE_SUM */
     uint32_t num_streams;    /* HIP streams buckets are spread over, [1, SHADOW_MAX_STREAMS] */
+    uint32_t optimizer;      /* SHADOW_OPT_ADAMW, SHADOW_OPT_ADAM or SHADOW_OPT_SGD                */
     uint64_t batch_bytes;    /* bucket scheduling: accepted buckets of a stream are buffered (host side,
                                 pointers only) until their gradient bytes (numel * elem size * W) reach
                                 this value, then folded by ONE launch; the iteration's last bucket,
@@ -192,7 +198,8 @@ int32_t shadow_apply_bucket(shadow_ctx* ctx, uint32_t bucket_id, const void* con
                             uint64_t step);
 
 /* Copy the replica at the last completed iteration: dst_* are device pointers
- * or pinned host pointers of arena_numel floats each (NULL = skip that array).
+ * or pinned host pointers of arena_numel floats each (NULL = skip that array;
+ * dst_v is ignored for SGD, which has no second state array).
  * The copies are enqueued after the iteration's last kernel and before any
  * later iteration's work; they have finished when shadow_sync returns.
  * *out_step (host pointer, may be NULL) receives the iteration count.

@@ -12,6 +12,9 @@ from .binding import (  # noqa: F401
     K_FOLD_ADAMW,
     K_FOLD_SUMSQ,
     K_NORM,
+    OPT_ADAM,
+    OPT_ADAMW,
+    OPT_SGD,
     REDUCE_MEAN,
     REDUCE_SUM,
     HParams,

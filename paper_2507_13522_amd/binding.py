@@ -15,6 +15,7 @@ from . import build as _build
 
 GRAD_F32, GRAD_BF16 = 0, 1
 REDUCE_MEAN, REDUCE_SUM = 0, 1
+OPT_ADAMW, OPT_ADAM, OPT_SGD = 0, 1, 2
 K_FOLD_ADAMW, K_FOLD_SUMSQ, K_NORM, K_ADAMW = 0, 1, 2, 3
 
 OK, EINVAL, EBUCKET, EDUP, ESTEP, EBUSY, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
@@ -28,7 +29,7 @@ class HParams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float), ("max_grad_norm", C.c_float), ("num_workers", C.c_uint32),
                 ("grad_dtype", C.c_uint32), ("reduce_op", C.c_uint32), ("num_streams", C.c_uint32),
-                ("batch_bytes", C.c_uint64)]
+                ("optimizer", C.c_uint32), ("batch_bytes", C.c_uint64)]
 
 
 class ShadowError(RuntimeError):
@@ -186,7 +187,7 @@ class Shadow:
                 raise ValueError("need hp.num_streams stream handles")
             sarr = (C.c_void_p * len(streams))(*[int(s) for s in streams])
         h = C.c_void_p()
-        _check(lib().shadow_init(C.byref(h), layout._h, C.byref(hp), d_param, d_m, d_v, d_reduced or None,
+        _check(lib().shadow_init(C.byref(h), layout._h, C.byref(hp), d_param, d_m, d_v or None, d_reduced or None,
                                  start_step, sarr), "shadow_init")
         self._h = h
         self._views = {}

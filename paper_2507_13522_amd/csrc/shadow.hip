@@ -177,6 +177,8 @@ void compute_scalars(const shadow_hparams& hp, uint64_t t, StepScalars& s)
     s.eps = hp.eps;
     s.inv_w = float(1.0 / double(hp.num_workers));
     s.mean = hp.reduce_op == SHADOW_REDUCE_MEAN ? 1u : 0u;
+    s.lr = hp.lr;
+    s.wd = hp.weight_decay;
 }
 
 // threads needed by a per-bucket kernel: one per 4 elements plus one for a ragged tail
@@ -243,10 +245,15 @@ struct ProfScope {
 template <bool BF16, int W>
 void launch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map, bool update)
 {
-    if (update)
-        k_fold_adamw<BF16, W><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, c->clip ? c->d_coef : nullptr, map, c->sc);
-    else
+    const float* coef = c->clip ? c->d_coef : nullptr;
+    if (!update)
         k_fold_sumsq<BF16, W><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->r, c->d_partial, c->sc);
+    else if (c->hp.optimizer == SHADOW_OPT_ADAMW)
+        k_fold_adamw<BF16, W, kAdamW><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc);
+    else if (c->hp.optimizer == SHADOW_OPT_ADAM)
+        k_fold_adamw<BF16, W, kAdam><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc);
+    else
+        k_fold_adamw<BF16, W, kSgd><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc);
 }
 
 template <bool BF16>
@@ -413,7 +420,7 @@ int32_t build_tables(shadow_ctx* c)
         const size_t bytes = (padded - end) * sizeof(float);
         HIP_TRY(hipMemset(c->p + end, 0, bytes));
         HIP_TRY(hipMemset(c->m + end, 0, bytes));
-        HIP_TRY(hipMemset(c->v + end, 0, bytes));
+        if (c->v) HIP_TRY(hipMemset(c->v + end, 0, bytes));
         if (c->r) HIP_TRY(hipMemset(c->r + end, 0, bytes));
     }
     if (c->clip) {
@@ -574,10 +581,13 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
 {
     if (!out) return SHADOW_EINVAL;
     *out = nullptr;
-    if (!layout || !hp || !d_param || !d_m || !d_v) return SHADOW_EINVAL;
-    if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) ||
-        !(hp->eps > 0.f) || !(hp->weight_decay >= 0.f) || std::isnan(hp->max_grad_norm))
+    if (!layout || !hp || !d_param || !d_m) return SHADOW_EINVAL;
+    if (hp->optimizer != SHADOW_OPT_ADAMW && hp->optimizer != SHADOW_OPT_ADAM && hp->optimizer != SHADOW_OPT_SGD) return SHADOW_EINVAL;
+    const bool sgd = hp->optimizer == SHADOW_OPT_SGD;
+    if (sgd ? d_v != nullptr : d_v == nullptr) return SHADOW_EINVAL;       // SGD keeps one state array only
+    if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->weight_decay >= 0.f) || std::isnan(hp->max_grad_norm))
         return SHADOW_EINVAL;
+    if (!sgd && (!(hp->beta2 >= 0.f && hp->beta2 < 1.f) || !(hp->eps > 0.f))) return SHADOW_EINVAL;
     if (hp->num_workers < 1 || hp->num_workers > SHADOW_MAX_WORKERS) return SHADOW_EINVAL;
     if (hp->grad_dtype != SHADOW_GRAD_F32 && hp->grad_dtype != SHADOW_GRAD_BF16) return SHADOW_EINVAL;
     if ((hp->grad_dtype == SHADOW_GRAD_BF16 ? 2u : 4u) != layout->grad_elem_bytes) return SHADOW_EINVAL;
@@ -725,7 +735,12 @@ int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const
                 const uint64_t blocks = (nvec + c->adamw_block - 1) / c->adamw_block;
                 for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
                     const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
-                    k_adamw<<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc);
+                    if (c->hp.optimizer == SHADOW_OPT_ADAMW)
+                        k_adamw<kAdamW><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc);
+                    else if (c->hp.optimizer == SHADOW_OPT_ADAM)
+                        k_adamw<kAdam><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc);
+                    else
+                        k_adamw<kSgd><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc);
                 }
                 if ((e = hipGetLastError()) != hipSuccess) return hip_fail("adamw kernel launch", e);
                 if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
@@ -752,7 +767,7 @@ int32_t shadow_snapshot(shadow_ctx* c, float* dst_param, float* dst_m, float* ds
     hipStream_t s0 = c->streams[0];
     if (dst_param) HIP_TRY(hipMemcpyAsync(dst_param, c->p, bytes, hipMemcpyDefault, s0));
     if (dst_m) HIP_TRY(hipMemcpyAsync(dst_m, c->m, bytes, hipMemcpyDefault, s0));
-    if (dst_v) HIP_TRY(hipMemcpyAsync(dst_v, c->v, bytes, hipMemcpyDefault, s0));
+    if (dst_v && c->v) HIP_TRY(hipMemcpyAsync(dst_v, c->v, bytes, hipMemcpyDefault, s0));
     rc = mark_boundary(c);
     if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
     if (out_step) *out_step = c->completed;

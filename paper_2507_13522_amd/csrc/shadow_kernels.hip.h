@@ -15,6 +15,9 @@
 //            m = b1*m + (1-b1)*g;  v = b2*v + ((1-b2)*g)*g;
 //            p -= step_size * (m / (sqrt(v)*isq + eps)),
 //            step_size = lr/(1-b1^t), isq = 1/sqrt(1-b2^t).
+//   Adam     as AdamW without the decay multiply, the L2 penalty joining the
+//            gradient first: g = g + wd*p on tensors with the flag.
+//   SGD      g = g + wd*p;  b = mu*b + g;  p -= lr*b   (b kept where Adam keeps m).
 //
 // Every float operation above is a separate IEEE-754 operation (the file is
 // compiled with -ffp-contract=off and correctly rounded divide/sqrt, denormals
@@ -75,7 +78,11 @@ __device__ __forceinline__ uint32_t bucket_of_block(const FoldBatch& fb, uint32_
 struct StepScalars {
     float beta1, beta2, omb1, omb2, decay, step_size, isq, eps, inv_w;
     uint32_t mean;
+    float lr, wd;      // as given (SGD step, L2 penalty of Adam and SGD)
 };
+
+// Optimizers (section 4.2.4: SGD, Adam and AdamW are functional).
+enum : int { kAdamW = 0, kAdam = 1, kSgd = 2 };
 
 // Weight-decay flag of every arena element: a byte per 1024-element tile
 // (0 = no decay, 1 = decay, 2 = the tile straddles tensors with different
@@ -94,25 +101,37 @@ __device__ __forceinline__ void store_once(T* p, T v) { __builtin_nontemporal_st
 
 __device__ __forceinline__ float bits_to_float(uint32_t b) { return __builtin_bit_cast(float, b); }
 
-__device__ __forceinline__ float decay_factor_of(const WdMap& map, uint64_t e, float decay)
+// One element.  flag: the tensor takes weight decay.  AdamW multiplies a masked element by
+// 1.0f (which returns it unchanged) instead of branching; the L2 penalty of Adam and SGD is
+// selected, not multiplied by zero, because g + 0*p is not always g (signed zeros, infinities).
+template <int OPT>
+__device__ __forceinline__ void opt_elem(float& p, float& m, float& v, float g, bool flag, const StepScalars& s)
+{
+    if constexpr (OPT == kAdamW) {
+        p = p * (flag ? s.decay : 1.0f);
+    } else {
+        const float pen = g + s.wd * p;
+        g = flag ? pen : g;
+    }
+    if constexpr (OPT == kSgd) {
+        m = s.beta1 * m + g;
+        p = p - s.lr * m;
+    } else {
+        m = s.beta1 * m + s.omb1 * g;
+        v = s.beta2 * v + (s.omb2 * g) * g;
+        float denom = sqrtf(v) * s.isq + s.eps;
+        p = p - s.step_size * (m / denom);
+    }
+}
+
+__device__ __forceinline__ bool decay_flag_of(const WdMap& map, uint64_t e)
 {
     uint32_t lo = 0, hi = map.num_runs;     // largest k with run_start[k] <= e
     while (hi - lo > 1) {
         uint32_t mid = (lo + hi) >> 1;
         if (map.run_start[mid] <= e) lo = mid; else hi = mid;
     }
-    return map.run_flag[lo] ? decay : 1.0f;
-}
-
-// x * 1.0f returns x unchanged, so a masked element is multiplied by one
-// instead of branching around the multiply.
-__device__ __forceinline__ void adamw_elem(float& p, float& m, float& v, float g, float dfac, const StepScalars& s)
-{
-    p = p * dfac;
-    m = s.beta1 * m + s.omb1 * g;
-    v = s.beta2 * v + (s.omb2 * g) * g;
-    float denom = sqrtf(v) * s.isq + s.eps;
-    p = p - s.step_size * (m / denom);
+    return map.run_flag[lo] != 0;
 }
 
 // ---- fold of 4 consecutive elements ---------------------------------------------------
@@ -192,25 +211,27 @@ __device__ __forceinline__ float fold1(const void* const* vp, uint32_t w_rt, uin
     return acc;
 }
 
-// AdamW on 4 consecutive arena elements starting at arena element e0 (multiple of 4).
-__device__ __forceinline__ void adamw4(float* p, float* m, float* v, uint64_t vec, uint64_t e0, const f32x4& g,
-                                       const WdMap& map, const StepScalars& s)
+// Optimizer step on 4 consecutive arena elements starting at arena element e0 (multiple of 4).
+// SGD has no second moment: v is never touched (it may be null).
+template <int OPT>
+__device__ __forceinline__ void update4(float* p, float* m, float* v, uint64_t vec, uint64_t e0, const f32x4& g,
+                                        const WdMap& map, const StepScalars& s)
 {
     f32x4 pp = load_once(reinterpret_cast<const f32x4*>(p) + vec);
     f32x4 mm = load_once(reinterpret_cast<const f32x4*>(m) + vec);
-    f32x4 vv = load_once(reinterpret_cast<const f32x4*>(v) + vec);
+    f32x4 vv = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (OPT != kSgd) vv = load_once(reinterpret_cast<const f32x4*>(v) + vec);
     const uint8_t mode = map.tile_mode[e0 >> kWdTileShift];
-    const float uniform = mode ? s.decay : 1.0f;
 #pragma unroll
     for (int k = 0; k < kVec; ++k) {
-        const float dfac = (mode != 2) ? uniform : decay_factor_of(map, e0 + k, s.decay);
+        const bool flag = (mode != 2) ? (mode != 0) : decay_flag_of(map, e0 + k);
         float pk = pp[k], mk = mm[k], vk = vv[k];
-        adamw_elem(pk, mk, vk, g[k], dfac, s);
+        opt_elem<OPT>(pk, mk, vk, g[k], flag, s);
         pp[k] = pk; mm[k] = mk; vv[k] = vk;
     }
     store_once(reinterpret_cast<f32x4*>(p) + vec, pp);
     store_once(reinterpret_cast<f32x4*>(m) + vec, mm);
-    store_once(reinterpret_cast<f32x4*>(v) + vec, vv);
+    if constexpr (OPT != kSgd) store_once(reinterpret_cast<f32x4*>(v) + vec, vv);
 }
 
 // ---- kernel: fold + AdamW in one pass (clipping off) ---------------------------------
@@ -218,7 +239,7 @@ __device__ __forceinline__ void adamw4(float* p, float* m, float* v, uint64_t ve
 // thread n/4 owns the (n mod 4) tail elements.
 // coef == nullptr: clipping off.  Otherwise the reduced gradient is multiplied by *coef first
 // (second fold of an iteration whose reduced gradient was not stored).
-template <bool BF16, int W>
+template <bool BF16, int W, int OPT>
 __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* __restrict__ p, float* __restrict__ m,
                                                           float* __restrict__ v, const float* __restrict__ coef, WdMap map,
                                                           StepScalars s)
@@ -231,14 +252,16 @@ __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* _
     if (vec < nvec) {
         f32x4 r = fold4<BF16, W>(vp, fb.w, vec, s);
         if (coef) r = r * (*coef);
-        adamw4(p + off, m + off, v + off, vec, off + (vec << 2), r, map, s);
+        update4<OPT>(p + off, m + off, OPT == kSgd ? nullptr : v + off, vec, off + (vec << 2), r, map, s);
     } else if (vec == nvec) {
         for (uint64_t e = nvec << 2; e < n; ++e) {
             float g = fold1<BF16>(vp, fb.w, e, s);
             if (coef) g = g * (*coef);
-            float pp = p[off + e], mm = m[off + e], vv = v[off + e];
-            adamw_elem(pp, mm, vv, g, decay_factor_of(map, off + e, s.decay), s);
-            p[off + e] = pp; m[off + e] = mm; v[off + e] = vv;
+            float pp = p[off + e], mm = m[off + e], vv = 0.f;
+            if constexpr (OPT != kSgd) vv = v[off + e];
+            opt_elem<OPT>(pp, mm, vv, g, decay_flag_of(map, off + e), s);
+            p[off + e] = pp; m[off + e] = mm;
+            if constexpr (OPT != kSgd) v[off + e] = vv;
         }
     }
 }
@@ -248,12 +271,15 @@ __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* _
 // launched (W = 1 bf16: 8 bytes), so the lane owns kVpl groups of 4 elements, blockDim apart
 // (every load instruction of a wave still covers one contiguous run), chosen so that a lane
 // reads at least 64 bytes.
+#ifndef SHADOW_FOLD_LANE_BYTES
+#define SHADOW_FOLD_LANE_BYTES 64
+#endif
 template <bool BF16, int W>
 constexpr int fold_vpl()
 {
     if (W <= 0) return 1;
     const int bytes = 4 * (BF16 ? 2 : 4) * W;
-    const int v = 64 / bytes;
+    const int v = SHADOW_FOLD_LANE_BYTES / bytes;
     return v < 1 ? 1 : (v > 8 ? 8 : v);
 }
 
@@ -354,6 +380,7 @@ __global__ __launch_bounds__(kNormBlock) void k_norm_finalize(const double* __re
 
 // ---- kernel: AdamW over the whole arena from the stored reduced gradient ---------------
 // block_base lets one logical sweep be issued as several launches (grid size limit).
+template <int OPT>
 __global__ __launch_bounds__(kMaxBlock) void k_adamw(const float* __restrict__ r, float* __restrict__ p, float* __restrict__ m,
                                                      float* __restrict__ v, uint64_t nvec, uint64_t block_base,
                                                      const float* __restrict__ coef, WdMap map, StepScalars s)
@@ -363,7 +390,7 @@ __global__ __launch_bounds__(kMaxBlock) void k_adamw(const float* __restrict__ r
     const float c = *coef;
     f32x4 g = load_once(reinterpret_cast<const f32x4*>(r) + vec);
     g = g * c;
-    adamw4(p, m, v, vec, vec << 2, g, map, s);
+    update4<OPT>(p, m, v, vec, vec << 2, g, map, s);
 }
 
 // ---- kernel: plain copy (bandwidth yardstick) ------------------------------------------

@@ -113,9 +113,9 @@ def oracle_layout(wl: synth.Workload) -> oracle.Layout:
                                wl.explicit_buckets)
 
 
-def oracle_hparams(wl: synth.Workload, mean: bool = True) -> oracle.HParams:
+def oracle_hparams(wl: synth.Workload, mean: bool = True, optimizer: str = "adamw") -> oracle.HParams:
     return oracle.HParams(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay,
-                          max_grad_norm=wl.max_grad_norm, mean=mean)
+                          max_grad_norm=wl.max_grad_norm, mean=mean, optimizer=optimizer)
 
 
 def lib_layout(wl: synth.Workload) -> sh.Layout:
@@ -123,12 +123,16 @@ def lib_layout(wl: synth.Workload) -> sh.Layout:
                      wl.explicit_buckets)
 
 
-def lib_hparams(wl: synth.Workload, num_streams: int = 2, mean: bool = True, batch_bytes: int = 0) -> sh.HParams:
+OPTIMIZERS = {"adamw": sh.OPT_ADAMW, "adam": sh.OPT_ADAM, "sgd": sh.OPT_SGD}
+
+
+def lib_hparams(wl: synth.Workload, num_streams: int = 2, mean: bool = True, batch_bytes: int = 0,
+                optimizer: str = "adamw") -> sh.HParams:
     return sh.HParams(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay,
                       max_grad_norm=wl.max_grad_norm, num_workers=wl.num_workers,
                       grad_dtype=sh.GRAD_BF16 if wl.grad_dtype == "bf16" else sh.GRAD_F32,
                       reduce_op=sh.REDUCE_MEAN if mean else sh.REDUCE_SUM, num_streams=num_streams,
-                      batch_bytes=batch_bytes)
+                      optimizer=OPTIMIZERS[optimizer], batch_bytes=batch_bytes)
 
 
 def assert_layouts_agree(ol: oracle.Layout, ll: sh.Layout) -> None:
@@ -149,7 +153,7 @@ class GpuShadow:
 
     def __init__(self, wl: synth.Workload, inputs: Inputs, num_streams: int = 2, mean: bool = True,
                  torch_streams: bool = False, resident_grads: bool = True, init_from=None, start_step: int = 0,
-                 advised_placement: bool = True, batch_bytes: int = 0, refold: bool = False):
+                 advised_placement: bool = True, batch_bytes: int = 0, refold: bool = False, optimizer: str = "adamw"):
         assert torch.cuda.is_available()
         self.wl, self.inputs = wl, inputs
         self.dev = torch.device("cuda:0")
@@ -184,10 +188,11 @@ class GpuShadow:
         self._stage = None
         if resident_grads:
             self._stage = torch.empty(max(L.staging_bytes(W), 256), dtype=torch.uint8, device=self.dev)
-        self.hp = lib_hparams(wl, num_streams, mean, batch_bytes)
+        self.hp = lib_hparams(wl, num_streams, mean, batch_bytes, optimizer)
+        self.optimizer = optimizer
         self._tstreams = [torch.cuda.Stream(device=self.dev) for _ in range(num_streams)] if torch_streams else None
         torch.cuda.synchronize()
-        self.ctx = sh.Shadow(L, self.hp, self.p.data_ptr(), self.m.data_ptr(), self.v.data_ptr(),
+        self.ctx = sh.Shadow(L, self.hp, self.p.data_ptr(), self.m.data_ptr(), None if optimizer == "sgd" else self.v.data_ptr(),
                              self.r.data_ptr() if self.r is not None else None, start_step,
                              [s.cuda_stream for s in self._tstreams] if self._tstreams else None)
         self._views = None
@@ -226,12 +231,12 @@ class GpuShadow:
 
 
 def run_oracle_full(wl: synth.Workload, inputs: Inputs, steps: int, orders=None, mean: bool = True, precision: str = "f32",
-                    on_step=None) -> oracle.OracleShadow:
+                    on_step=None, optimizer: str = "adamw") -> oracle.OracleShadow:
     """Whole-model oracle run (small and medium workloads)."""
     lay = oracle_layout(wl)
     starts = lay.logical_starts()
     params = [inputs.param_np(s, b.numel) for s, b in zip(starts, lay.buckets)]
-    orc = oracle.OracleShadow(lay, oracle_hparams(wl, mean), params, precision=precision)
+    orc = oracle.OracleShadow(lay, oracle_hparams(wl, mean, optimizer), params, precision=precision)
     for t in range(1, steps + 1):
         grads = {b: [inputs.grad_np(t, w, starts[b], lay.buckets[b].numel) for w in range(wl.num_workers)]
                  for b in range(len(lay.buckets))}

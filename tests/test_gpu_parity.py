@@ -29,13 +29,13 @@ def custom(name, sizes_flags, W, dtype, clip=0.0, cap=1 << 16, steps=3, dist="no
 
 
 def check_against_oracle(wl, steps=None, num_streams=2, mean=True, every_step=True, exact=True, torch_streams=False,
-                         batch_bytes=0, refold=False):
+                         batch_bytes=0, refold=False, optimizer="adamw"):
     """Run both sides on the same inputs and compare param, m, v of every bucket."""
     steps = steps or wl.steps
     inp = Inputs(wl)
     assert_layouts_agree(oracle_layout(wl), lib_layout(wl))
     g = GpuShadow(wl, inp, num_streams=num_streams, mean=mean, torch_streams=torch_streams, batch_bytes=batch_bytes,
-                  refold=refold)
+                  refold=refold, optimizer=optimizer)
     worst = {}
 
     def on_step(t, orc):
@@ -51,7 +51,7 @@ def check_against_oracle(wl, steps=None, num_streams=2, mean=True, every_step=Tr
                 assert np.float32(c) == orc.last_coef, (c, orc.last_coef)
                 assert abs(S - orc.last_sumsq) <= 1e-12 * orc.last_sumsq
 
-    run_oracle_full(wl, inp, steps, mean=mean, on_step=on_step)
+    run_oracle_full(wl, inp, steps, mean=mean, on_step=on_step, optimizer=optimizer)
     assert g.ctx.step() == (steps, 0)
     g.close()
     return worst
@@ -110,6 +110,17 @@ def test_clip_without_scratch_folds_twice(W, dtype, batch_bytes):
     many = custom("refold-many", [(int(n), bool(n % 3)) for n in np.random.default_rng(W).integers(1, 2000, 90)], W, dtype,
                   clip=0.003, cap=3000, steps=2)
     check_against_oracle(many, num_streams=3, batch_bytes=batch_bytes, refold=True)
+
+
+@pytest.mark.parametrize("optimizer", ["adam", "sgd"])
+@pytest.mark.parametrize("W,dtype,clip,refold", [(8, "bf16", 0.0, False), (8, "bf16", 0.01, False), (1, "bf16", 0.01, True),
+                                                 (5, "f32", 0.01, False), (4, "f32", 0.0, False)])
+def test_other_functional_optimizers(optimizer, W, dtype, clip, refold):
+    """Adam (L2 penalty in the gradient) and momentum SGD (section 4.2.4) against the oracle, bit for bit."""
+    say("case optimizer", optimizer, W, dtype, clip, refold)
+    wl = custom("opt-" + optimizer, RAGGED, W, dtype, clip=clip, cap=200_000, steps=5, random_arrival=True, wd=0.1,
+                lr=1e-3 if optimizer == "adam" else 0.05)
+    check_against_oracle(wl, num_streams=2, batch_bytes=1 << 20, refold=refold, optimizer=optimizer)
 
 
 def test_sum_reduce_and_student_t():
