@@ -3,7 +3,7 @@
 
 A step is one whole iteration of the hot path over one batch of synthetic
 gradients: every bucket of the model is folded over its W worker views, the
-global gradient norm is formed, and AdamW is applied to the fp32 replica.
+global gradient norm is formed, and the optimizer (AdamW) is applied to the fp32 replica.
 Inputs (replica and all W views of every bucket) are resident in HBM before
 the timed region.  Prints ONE JSON line.
 
@@ -50,7 +50,9 @@ KERNEL_NAMES = {0: "k_fold_adamw", 1: "k_fold_sumsq", 2: "k_norm_finalize", 3: "
 
 
 def algorithmic_bytes_per_param(wl, refold: bool = False, optimizer: str = "adamw") -> dict:
-    """Bytes the method must move per parameter and step, by kernel (measurement)."""
+    """Bytes the method must move per parameter and step, by kernel: every gradient view read once (W*G), p, m
+    (and v) read and written once, and with clipping the fp32 reduced gradient written and read once (or the views
+    read a second time when no scratch arena is given)."""
     g = wl.grad_bytes * wl.num_workers
     st = 16 if optimizer == "sgd" else 24        # state read + written: p, m (, v)
     if wl.max_grad_norm > 0 and refold:          # views folded twice, reduced gradient never stored
