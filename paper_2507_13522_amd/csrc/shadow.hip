@@ -21,9 +21,9 @@ thread_local std::string g_hip_error;
 
 struct Tunables {
     int64_t fold_block = 1024;    // threads per block of the per-bucket kernels
-    int64_t adamw_block = 512;    // threads per block of the whole-arena AdamW sweep
+    int64_t adamw_block = 256;    // threads per block of the whole-arena AdamW sweep
     int64_t fold_lds = 0;         // bytes of LDS reserved per block only to cap the waves resident per CU
-    int64_t adamw_lds = 65536;    // 2 blocks of 512 threads (16 waves) per CU
+    int64_t adamw_lds = 40960;    // 4 blocks of 256 threads (16 waves) per CU
 } g_tune;
 
 constexpr uint64_t kMaxThreadsPerLaunch = 1ull << 31;
@@ -81,7 +81,7 @@ struct shadow_ctx {
     double* d_partial = nullptr;
     double* d_stage1 = nullptr;
     uint32_t nstage1 = 0;
-    uint32_t fold_block = 1024, adamw_block = 512, fold_lds = 0, adamw_lds = 65536;
+    uint32_t fold_block = 1024, adamw_block = 256, fold_lds = 0, adamw_lds = 40960;
     float* d_coef = nullptr;
     double* d_sumsq = nullptr;
     std::vector<uint32_t> slot_base, slot_count;

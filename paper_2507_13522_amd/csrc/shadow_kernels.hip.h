@@ -349,7 +349,7 @@ __device__ __forceinline__ double block_sum(double x, double* lds)
 // ---- kernels: norm and clip coefficient, two stages with fixed summation order ---------
 // stage 1: block b sums slots [b*chunk, (b+1)*chunk), lane t taking every blockDim-th slot
 constexpr int kNormBlock = 1024;
-constexpr uint32_t kNormChunk = kNormBlock * 16;
+constexpr uint32_t kNormChunk = kNormBlock * 4;
 __global__ __launch_bounds__(kNormBlock) void k_norm_stage1(const double* __restrict__ partial, uint32_t nslots,
                                                             double* __restrict__ stage1)
 {
