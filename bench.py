@@ -120,6 +120,9 @@ def main() -> int:
     ap.add_argument("--refold", action="store_true",
                     help="clipping without a scratch arena: fold the views twice instead of storing the reduced gradient")
     ap.add_argument("--optimizer", default="adamw", choices=["adamw", "adam", "sgd"])
+    ap.add_argument("--ingest-slots", type=int, default=0,
+                    help="hand the buckets over as pinned HOST views through a device ring of this many slots "
+                         "(PCIe-inclusive rate; never the headline value)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fold-block", type=int, default=0)
     ap.add_argument("--adamw-block", type=int, default=0)
@@ -149,13 +152,30 @@ def main() -> int:
 
     wl = synth.get_workload(args.workload)
     inputs = Inputs(wl, period=TILE_PERIOD)
-    g = GpuShadow(wl, inputs, num_streams=streams, batch_bytes=batch_bytes, refold=args.refold, optimizer=args.optimizer)
+    ingest = args.ingest_slots > 0
+    g = GpuShadow(wl, inputs, num_streams=streams, batch_bytes=batch_bytes, refold=args.refold, optimizer=args.optimizer,
+                  resident_grads=not ingest)
     P = g.layout.num_params
-    g.fill_grads(1)            # the same resident views serve every timed step (values do not affect timing)
+    if ingest:
+        # one pinned host buffer per worker, as long as the largest bucket, serves every bucket (values do not
+        # affect timing); the device ring holds ingest_slots buckets
+        nmax = max(n for _, n, _ in g.buckets)
+        view_bytes = (nmax * wl.grad_bytes + 255) // 256 * 256
+        host = [torch.zeros(view_bytes, dtype=torch.uint8).pin_memory() for _ in range(wl.num_workers)]
+        ring = torch.empty(args.ingest_slots * wl.num_workers * view_bytes, dtype=torch.uint8, device="cuda:0")
+        g.ctx.ingest_attach(ring.data_ptr(), ring.numel())
+        hv = g.ctx.views_array([h.data_ptr() for h in host])
+
+        def run_step(s):
+            for b in range(len(g.buckets)):
+                g.ctx.ingest_bucket(b, hv, s)
+    else:
+        g.fill_grads(1)        # the same resident views serve every timed step (values do not affect timing)
+        run_step = g.apply_step
     step = 0
     for _ in range(args.warmup):
         step += 1
-        g.apply_step(step)
+        run_step(step)
     g.ctx.sync()
     if args.copy_probe_mib:
         nbytes = args.copy_probe_mib << 20
@@ -170,7 +190,7 @@ def main() -> int:
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step += 1
-        g.apply_step(step)
+        run_step(step)
     g.ctx.sync()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -211,7 +231,8 @@ def main() -> int:
                                f"{args.optimizer}" + (f" + global-norm clip at {wl.max_grad_norm}" if wl.max_grad_norm > 0 else ""),
                    "num_params": P, "num_buckets": len(g.buckets), "num_workers": wl.num_workers,
                    "grad_dtype": wl.grad_dtype, "streams": streams,
-                   "batch_bytes": batch_bytes, "refold": bool(args.refold), "optimizer": args.optimizer},
+                   "batch_bytes": batch_bytes, "refold": bool(args.refold), "optimizer": args.optimizer,
+                   "ingest_slots": args.ingest_slots},
         "hbm_GBps": total_gbs,
         "hbm_frac_of_peak": total_gbs / HBM_PEAK_GBS,
         "bytes_per_param": bpp["total"],

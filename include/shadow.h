@@ -197,6 +197,22 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
 int32_t shadow_apply_bucket(shadow_ctx* ctx, uint32_t bucket_id, const void* const* d_grad_views,
                             uint64_t step);
 
+/* Ingest from host memory: the analogue of the shadow node's receive path, which copies
+ * reassembled buckets from network buffers into the framework's tensors (section 5).
+ * shadow_ingest_attach lends the context a device ring (d_ring: device pointer, 256-byte
+ * aligned, ring_bytes >= W * (largest bucket's gradient bytes rounded up to 256); borrowed until
+ * shadow_destroy); it is cut into slots that each hold the W views of one bucket (at most 64
+ * slots are used).  shadow_ingest_bucket copies the W HOST views (h_grad_views: host array of
+ * W host pointers, pinned memory for the copies to be asynchronous) of a bucket into the next
+ * slot on a copy stream of the library's own, orders the bucket's fold behind the copy on the
+ * bucket's stream and launches it at once (batch_bytes does not apply), so that the copy of
+ * one bucket overlaps the fold of the previous ones; a slot is overwritten only after its fold
+ * has run.  The host views must stay unchanged until shadow_sync returns.  Same step / bucket
+ * rules and errors as shadow_apply_bucket; not available when clipping runs without a scratch
+ * arena (EINVAL).  Both ways of delivering buckets may be mixed within an iteration. */
+int32_t shadow_ingest_attach(shadow_ctx* ctx, void* d_ring, uint64_t ring_bytes);
+int32_t shadow_ingest_bucket(shadow_ctx* ctx, uint32_t bucket_id, const void* const* h_grad_views, uint64_t step);
+
 /* Copy the replica at the last completed iteration: dst_* are device pointers
  * or pinned host pointers of arena_numel floats each (NULL = skip that array;
  * dst_v is ignored for SGD, which has no second state array).

@@ -56,6 +56,8 @@ _SIGS = {
     "shadow_layout_staging_view": [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64)],
     "shadow_init": [C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(HParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p)],
     "shadow_apply_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64],
+    "shadow_ingest_attach": [C.c_void_p, C.c_void_p, C.c_uint64],
+    "shadow_ingest_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64],
     "shadow_snapshot": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64)],
     "shadow_sync": [C.c_void_p],
     "shadow_destroy": [C.c_void_p],
@@ -205,6 +207,14 @@ class Shadow:
         if not isinstance(views, C.Array):
             views = self.views_array(views)
         return int(lib().shadow_apply_bucket(self._h, bucket_id, views, step))
+
+    def ingest_attach(self, d_ring: int, ring_bytes: int) -> None:
+        _check(lib().shadow_ingest_attach(self._h, d_ring, ring_bytes), "shadow_ingest_attach")
+
+    def ingest_bucket(self, bucket_id: int, host_views, step: int) -> None:
+        if not isinstance(host_views, C.Array):
+            host_views = self.views_array(host_views)
+        _check(lib().shadow_ingest_bucket(self._h, bucket_id, host_views, step), "shadow_ingest_bucket")
 
     def snapshot(self, dst_param: Optional[int], dst_m: Optional[int], dst_v: Optional[int]) -> int:
         st = C.c_uint64()

@@ -101,6 +101,13 @@ struct shadow_ctx {
     struct Pending { uint32_t bucket; const void* ptr[kMaxWorkers]; };
     std::vector<std::vector<Pending>> pending;
     std::vector<uint64_t> pending_bytes;
+    // ingest from host memory: device ring of slots, each holding the W views of one bucket
+    char* ring = nullptr;
+    uint64_t slot_bytes = 0, view_stride = 0;
+    uint32_t ring_slots = 0, ring_next = 0;
+    hipStream_t copy_stream = nullptr;
+    std::vector<hipEvent_t> copied_ev, consumed_ev;
+    std::vector<uint8_t> consumed_valid;
     // profiling
     bool profile = false;
     struct Span { hipEvent_t a, b; };
@@ -367,6 +374,9 @@ void free_ctx(shadow_ctx* c)
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->join_ev) if (e) (void)hipEventDestroy(e);
     if (c->boundary_ev) (void)hipEventDestroy(c->boundary_ev);
+    for (hipEvent_t e : c->copied_ev) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->consumed_ev) if (e) (void)hipEventDestroy(e);
+    if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
     if (c->own_streams) for (hipStream_t s : c->streams) if (s) (void)hipStreamDestroy(s);
     (void)hipFree(c->d_tile_mode);
     (void)hipFree(c->d_run_start);
@@ -654,13 +664,25 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
     return SHADOW_OK;
 }
 
-int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const* d_grad_views, uint64_t step)
+}  // extern "C"
+
+namespace {
+
+// the checks every delivery of a bucket must pass before anything is enqueued (section 4.1: exactly once per iteration)
+int32_t precheck_bucket(const shadow_ctx* c, uint32_t bucket_id, const void* const* views, uint64_t step)
 {
-    if (!c || !d_grad_views) return SHADOW_EINVAL;
+    if (!c || !views) return SHADOW_EINVAL;
     if (c->poisoned) return SHADOW_EHIP;
     if (bucket_id >= c->lay.buckets.size()) return SHADOW_EBUCKET;
     if (step != c->completed + 1) return SHADOW_ESTEP;
     if (c->arrived[bucket_id]) return SHADOW_EDUP;
+    return SHADOW_OK;
+}
+
+int32_t apply_bucket_impl(shadow_ctx* c, uint32_t bucket_id, const void* const* d_grad_views, uint64_t step, bool launch_now)
+{
+    int32_t pre = precheck_bucket(c, bucket_id, d_grad_views, step);
+    if (pre != SHADOW_OK) return pre;
     const uint32_t W = c->hp.num_workers;
     shadow_ctx::Pending pend{};
     pend.bucket = bucket_id;
@@ -700,7 +722,7 @@ int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const
     if (last) {
         const int32_t rc = flush_all(c);
         if (rc != SHADOW_OK) return rc;
-    } else if (c->pending_bytes[sid] >= c->hp.batch_bytes) {
+    } else if (launch_now || c->pending_bytes[sid] >= c->hp.batch_bytes) {
         const int32_t rc = flush_stream(c, sid);
         if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
     }
@@ -753,6 +775,88 @@ int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const
         c->arrived_count = 0;
         c->completed = step;
     }
+    return SHADOW_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const* d_grad_views, uint64_t step)
+{
+    return apply_bucket_impl(c, bucket_id, d_grad_views, step, /*launch_now=*/false);
+}
+
+int32_t shadow_ingest_attach(shadow_ctx* c, void* d_ring, uint64_t ring_bytes)
+{
+    if (!c || !d_ring || !aligned(d_ring, 256)) return SHADOW_EINVAL;
+    if (c->refold) return SHADOW_EINVAL;          // folding twice needs the whole iteration's views to persist
+    if (c->arrived_count != 0) return SHADOW_EBUSY;
+    if (c->ring) return SHADOW_EINVAL;
+    uint64_t max_numel = 0;
+    for (const BucketL& b : c->lay.buckets) if (b.numel > max_numel) max_numel = b.numel;
+    const uint64_t view_stride = (max_numel * c->lay.grad_elem_bytes + 255) / 256 * 256;
+    const uint64_t slot_bytes = view_stride * c->hp.num_workers;
+    const uint64_t nslots = ring_bytes / slot_bytes;
+    if (nslots < 1) return SHADOW_EINVAL;
+    const uint32_t n = uint32_t(nslots > 64 ? 64 : nslots);
+    HIP_TRY(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+    try {
+        c->copied_ev.assign(n, nullptr);
+        c->consumed_ev.assign(n, nullptr);
+        c->consumed_valid.assign(n, 0);
+    } catch (const std::bad_alloc&) {
+        return SHADOW_ENOMEM;
+    }
+    for (uint32_t i = 0; i < n; ++i) {
+        HIP_TRY(hipEventCreateWithFlags(&c->copied_ev[i], hipEventDisableTiming));
+        HIP_TRY(hipEventCreateWithFlags(&c->consumed_ev[i], hipEventDisableTiming));
+    }
+    c->ring = static_cast<char*>(d_ring);
+    c->view_stride = view_stride;
+    c->slot_bytes = slot_bytes;
+    c->ring_slots = n;
+    c->ring_next = 0;
+    return SHADOW_OK;
+}
+
+int32_t shadow_ingest_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const* h_grad_views, uint64_t step)
+{
+    int32_t pre = precheck_bucket(c, bucket_id, h_grad_views, step);
+    if (pre != SHADOW_OK) return pre;
+    if (!c->ring) return SHADOW_EINVAL;
+    const uint32_t W = c->hp.num_workers;
+    for (uint32_t w = 0; w < W; ++w)
+        if (!h_grad_views[w]) return SHADOW_EINVAL;
+    // ---- nothing above changed any state ----
+    const BucketL& b = c->lay.buckets[bucket_id];
+    const uint64_t bytes = b.numel * c->lay.grad_elem_bytes;
+    const uint32_t slot = c->ring_next;
+    char* base = c->ring + uint64_t(slot) * c->slot_bytes;
+    hipStream_t st = c->streams[bucket_id % c->streams.size()];
+    auto fail = [&](const char* what, hipError_t e) {
+        g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+        c->poisoned = true;
+        return int32_t(SHADOW_EHIP);
+    };
+    hipError_t e;
+    // the slot's previous occupant must have been folded before it is overwritten
+    if (c->consumed_valid[slot] && (e = hipStreamWaitEvent(c->copy_stream, c->consumed_ev[slot], 0)) != hipSuccess)
+        return fail("hipStreamWaitEvent", e);
+    const void* dev_views[kMaxWorkers];
+    for (uint32_t w = 0; w < W; ++w) {
+        char* dst = base + uint64_t(w) * c->view_stride;
+        if ((e = hipMemcpyAsync(dst, h_grad_views[w], bytes, hipMemcpyHostToDevice, c->copy_stream)) != hipSuccess)
+            return fail("hipMemcpyAsync", e);
+        dev_views[w] = dst;
+    }
+    if ((e = hipEventRecord(c->copied_ev[slot], c->copy_stream)) != hipSuccess) return fail("hipEventRecord", e);
+    if ((e = hipStreamWaitEvent(st, c->copied_ev[slot], 0)) != hipSuccess) return fail("hipStreamWaitEvent", e);
+    const int32_t rc = apply_bucket_impl(c, bucket_id, dev_views, step, /*launch_now=*/true);
+    if (rc != SHADOW_OK) { c->poisoned = true; return rc; }      // cannot happen after the precheck except for HIP failures
+    if ((e = hipEventRecord(c->consumed_ev[slot], st)) != hipSuccess) return fail("hipEventRecord", e);
+    c->consumed_valid[slot] = 1;
+    c->ring_next = (slot + 1) % c->ring_slots;
     return SHADOW_OK;
 }
 

@@ -205,6 +205,100 @@ def test_ieee_divide_sqrt_denormals_bruteforce():
         ctx.destroy()
 
 
+def _same_bits_or_nan(a, b):
+    return bool(np.all((a.view(np.uint32) == b.view(np.uint32)) | (np.isnan(a) & np.isnan(b))))
+
+
+@pytest.mark.parametrize("clip", [0.0, 0.01])
+def test_non_finite_gradients_propagate(clip):
+    """No special handling of Inf/NaN gradients: they propagate exactly as in the oracle (without clipping only the
+    poisoned elements change; with clipping an infinite norm gives c = 0 and 0*Inf = NaN in the poisoned element)."""
+    say("case non-finite", clip)
+    wl = custom("nonfinite", [(5000, True), (777, False), (4099, True)], 2, "f32", clip=clip, cap=20_000, steps=2)
+    inp = Inputs(wl)
+    g = GpuShadow(wl, inp, num_streams=2)
+    lay = oracle_layout(wl)
+    starts = lay.logical_starts()
+    orc = oracle.OracleShadow(lay, oracle.HParams(lr=wl.lr, weight_decay=wl.weight_decay, max_grad_norm=clip),
+                              [inp.param_np(s, b.numel) for s, b in zip(starts, lay.buckets)])
+    poison = {(0, 0, 17): np.inf, (1, 1, 5): -np.inf, (0, 1, 4000): np.nan}      # (bucket, worker, element) -> value
+    for t in (1, 2):
+        g.fill_grads(t)
+        grads = {b: [inp.grad_np(t, w, starts[b], lay.buckets[b].numel) for w in range(2)] for b in range(len(lay.buckets))}
+        if t == 1:
+            for (b, w, e), val in poison.items():
+                if b < len(lay.buckets) and e < lay.buckets[b].numel:
+                    grads[b][w][e] = val
+                    g.view(b, w)[e] = float(val)
+        torch.cuda.synchronize()
+        g.apply_step(t)
+        g.ctx.sync()
+        orc.step(grads)
+    n_bad = 0
+    for b in range(len(lay.buckets)):
+        got = g.bucket_state(b)
+        for x, y in zip(got, (orc.p[b], orc.m[b], orc.v[b])):
+            assert _same_bits_or_nan(x, y)
+            n_bad += int(np.count_nonzero(~np.isfinite(x)))
+    assert n_bad > 0
+    if clip == 0.0:
+        assert n_bad <= 3 * len(poison) * 1        # only the poisoned elements (p, m, v each)
+    g.close()
+
+
+@pytest.mark.parametrize("slots,streams,clip", [(1, 1, 0.01), (2, 2, 0.01), (5, 3, 0.0)])
+def test_ingest_from_pinned_host(slots, streams, clip):
+    """Buckets handed over as HOST views go through the device ring (copy overlapping the folds of earlier buckets);
+    results equal the oracle's, also when host and device deliveries are mixed within an iteration."""
+    say("case ingest", slots, streams, clip)
+    W = 4
+    wl = custom("ingest", RAGGED, W, "bf16", clip=clip, cap=150_000, steps=4, random_arrival=True)
+    inp = Inputs(wl)
+    g = GpuShadow(wl, inp, num_streams=streams)
+    B = len(g.buckets)
+    nmax = max(n for _, n, _ in g.buckets)
+    slot_bytes = W * ((nmax * 2 + 255) // 256 * 256)
+    ring = torch.empty(slots * slot_bytes, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(sh.ShadowError):
+        g.ctx.ingest_bucket(0, [1, 2, 3, 4], 1)                      # no ring attached yet
+    with pytest.raises(sh.ShadowError):
+        g.ctx.ingest_attach(ring.data_ptr(), slot_bytes - 256)       # smaller than one bucket's views
+    g.ctx.ingest_attach(ring.data_ptr(), ring.numel())
+    with pytest.raises(sh.ShadowError):
+        g.ctx.ingest_attach(ring.data_ptr(), ring.numel())           # only once
+    lay = oracle_layout(wl)
+    starts = lay.logical_starts()
+    orc = oracle.OracleShadow(lay, oracle.HParams(lr=wl.lr, weight_decay=wl.weight_decay, max_grad_norm=clip),
+                              [inp.param_np(s, b.numel) for s, b in zip(starts, lay.buckets)])
+    for t in range(1, 5):
+        host = {b: [torch.from_numpy(inp.grad_np(t, w, starts[b], lay.buckets[b].numel).view(np.int16)).pin_memory()
+                    for w in range(W)] for b in range(B)}
+        g.fill_grads(t)
+        for b in synth.arrival_order(wl.seed, t, B):
+            if (b + t) % 3 == 0:
+                g.ctx.apply_bucket(b, g._views[b], t)                # device views
+            else:
+                g.ctx.ingest_bucket(b, [h.data_ptr() for h in host[b]], t)
+        assert g.ctx.try_apply_bucket(0, g._views[0], t) == binding.ESTEP   # iteration t is complete
+        g.ctx.sync()
+        orc.step({b: [h.numpy().view(np.uint16) for h in host[b]] for b in range(B)})
+        for b in range(B):
+            assert_state_matches(g.bucket_state(b), (orc.p[b], orc.m[b], orc.v[b]), f"ingest step {t} bucket {b}")
+    g.close()
+    # a replica that folds twice (no scratch arena) cannot use the ring: the views would have to outlive their slots
+    wl2 = custom("ingest-refold", RAGGED[:5], 1, "bf16", clip=0.01, cap=150_000, steps=1)
+    g2 = GpuShadow(wl2, Inputs(wl2), refold=True)
+    with pytest.raises(sh.ShadowError):
+        g2.ctx.ingest_attach(ring.data_ptr(), ring.numel())
+    g2.close()
+
+
+def test_sixteen_streams():
+    say("case 16 streams")
+    wl = custom("s16", RAGGED, 4, "bf16", clip=0.01, cap=60_000, steps=3, random_arrival=True)
+    check_against_oracle(wl, num_streams=16, batch_bytes=200_000)
+
+
 def test_order_partition_and_stream_invariance():
     """Functional optimizer (section 4.2.4): the result does not depend on bucket arrival order,
     on how tensors are split into buckets, or on how many streams carry the buckets."""

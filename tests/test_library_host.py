@@ -71,6 +71,12 @@ def test_layout_rejects_bad_arguments():
         sh.Layout([(5, True)], 2, 0)
     with pytest.raises(sh.ShadowError):
         sh.Layout([(5, True), (6, True)], 2, 0, [0, 2])      # ids not dense
+    with pytest.raises(sh.ShadowError):
+        sh.Layout([((1 << 48) + 1, True)], 2, 1 << 20)           # beyond the largest supported tensor
+    with pytest.raises(sh.ShadowError):
+        sh.Layout([(1 << 47, True), (1 << 47, True), (8, True)], 2, 1 << 20)   # total beyond 2^48 elements
+    big = sh.Layout([(1 << 40, True), (3, False)], 2, 1 << 20)   # sizes far beyond 32 bits are planned exactly
+    assert big.num_params == (1 << 40) + 3 and big.num_buckets == 2 and big.bucket(1) == (64, 1 << 40, 1)
     lay = sh.Layout([(5, True)], 2, 100)
     with pytest.raises(sh.ShadowError) as e:
         lay.bucket(1)
