@@ -213,8 +213,6 @@ uint32_t sumsq_vpl(const shadow_hparams& hp)
 }
 
 // blocks of a bucket's launch: update == false is the fold + sum-of-squares kernel
-uint32_t bucket_blocks(const shadow_ctx* c, uint64_t numel, bool update);
-
 uint32_t bucket_blocks(const shadow_ctx* c, uint64_t numel, bool update)
 {
     const uint32_t vpl = update ? 1u : sumsq_vpl(c->hp);
