@@ -124,6 +124,7 @@ def main() -> int:
                     help="hand the buckets over as pinned HOST views through a device ring of this many slots "
                          "(PCIe-inclusive rate; never the headline value)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-yardstick", action="store_true", help="skip timing the plain copy kernel")
     ap.add_argument("--fold-block", type=int, default=0)
     ap.add_argument("--adamw-block", type=int, default=0)
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -185,6 +186,22 @@ def main() -> int:
         sh.shadow_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, 0)
         torch.cuda.synchronize()
         del src, dst
+    # yardstick: the library's plain copy kernel over 2 GiB (read 2 GiB + write 2 GiB), timed with events
+    yard = None
+    if not args.no_yardstick:
+        nb = 2 << 30
+        src = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        sh.shadow_copy_probe(dst.data_ptr(), src.data_ptr(), nb, 0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            sh.shadow_copy_probe(dst.data_ptr(), src.data_ptr(), nb, 0)
+        e1.record()
+        torch.cuda.synchronize()
+        yard = 5 * 2 * nb / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
     torch.cuda.synchronize()
     g.ctx.profile_enable(True)
     t0 = time.perf_counter()
@@ -236,6 +253,8 @@ def main() -> int:
         "hbm_GBps": total_gbs,
         "hbm_frac_of_peak": total_gbs / HBM_PEAK_GBS,
         "bytes_per_param": bpp["total"],
+        "copy_kernel_GBps": yard,
+        "hbm_frac_of_copy_kernel": (total_gbs / yard) if yard else None,
         "kernels": kernels,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name, dom),
