@@ -132,7 +132,7 @@ def main() -> int:
                          "yardstick for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no sharding across GPUs, no collectives); run with --gpus 1",
+        print("bench.py: the shadow update runs on ONE GPU (no sharding across GPUs, no collectives); run with --gpus 1",
               file=sys.stderr)
         return 2
 
