@@ -63,7 +63,7 @@ def algorithmic_bytes_per_param(wl, refold: bool = False, optimizer: str = "adam
 
 
 def cpu_baseline(wl, inputs, target_seconds: float = 15.0, optimizer: str = "adamw") -> dict:
-    """Time the oracle, as it stands, on this box's host cores over a bounded sample of the same workload."""
+    """Time the oracle, as it stands, on this machine's host cores over a bounded sample of the same workload."""
     import numpy as np
     import oracle
     from harness import oracle_hparams, oracle_layout
