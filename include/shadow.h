@@ -118,24 +118,49 @@ int32_t shadow_layout_bucket(const shadow_layout* layout, uint32_t bucket, uint6
 int32_t shadow_layout_tensor(const shadow_layout* layout, uint32_t tensor, uint32_t* bucket,
                              uint64_t* offset_in_bucket, uint64_t* arena_offset);
 
-/* Placement advice (host only).  On MI355X the speed of a kernel that streams
- * several arrays at once depends on how far apart the arrays lie: HBM bank
- * hashing keeps arrays that are a power-of-two distance apart (in one device
- * allocation) on disjoint banks, and the W views of one bucket stream best when
- * they lie close together.  Measured on the 7B layout: whole-arena AdamW sweep
- * 29.3 ms with the four arenas 32 GiB apart vs 31-33 ms back to back or in
- * separate allocations; fold 6.4 TB/s with bucket-major views vs 6.05 TB/s
- * with worker-major buffers.  Nothing below is required for correctness.
+/* Placement advice (host only; nothing below is required for correctness).
+ * On MI355X the speed of a kernel that streams several arrays at once depends
+ * on where in the 288 GiB of HBM the arrays lie.  Measured: the memory behaves
+ * as three regions of 96 GiB; arrays that are WRITTEN at the same time should
+ * not all lie in one region (whole-arena AdamW sweep at 7B: 33 ms with param,
+ * m and v in one region, 29 ms with two of them in one region and the third
+ * in the next), and a written array should not share its region with many
+ * arrays that are read at the same time (fold of 16 views: 8.2 ms with the
+ * reduced-gradient arena in the region of the views, 7.3 ms with it in
+ * another).  The W views of one bucket stream best close together
+ * (bucket-major: 6.4 TB/s, one arena-sized buffer per worker: 6.05 TB/s).
+ *
+ * shadow_layout_device_plan: byte offsets for param, m, v, the scratch arena
+ * and the staging buffer inside ONE device allocation of block_bytes
+ * (256 GiB).  Made first in a process, such an allocation is one naturally
+ * aligned block of the driver's allocator, so offsets inside it are physical
+ * offsets: the scratch arena, param and m end the first region, v starts the
+ * second, the staging buffer follows v.  with_scratch / with_staging: nonzero
+ * when the caller wants those parts (their offsets are 0 otherwise).
+ * SHADOW_ENOMEM when the parts do not fit this scheme (the caller then places
+ * them itself, e.g. by the stride below).
  *
  * shadow_layout_arena_stride: recommended distance in BYTES between the starts
  * of param, m, v (and the scratch arena) when they are carved from one device
  * allocation: the smallest power of two >= the arena's size (at least 2 MiB).
  *
  * shadow_layout_staging_*: a bucket-major staging buffer for the gradient
- * views: bucket 0's W views, then bucket 1's ..., every view starting on a
- * 2 MiB boundary (256 B for views shorter than 2 MiB).  _bytes gives the size
- * of the whole buffer, _view the byte offset of worker `worker`'s view of
- * `bucket`. */
+ * views: bucket 0's W views, then bucket 1's ..., every bucket starting on a
+ * 2 MiB boundary.  Views of 2 MiB or more lie a multiple of 2 MiB plus 4 KiB
+ * apart (worker w's view starts w * 4 KiB past a 2 MiB boundary), so that the
+ * W reads of one element do not meet in one DRAM channel; shorter views lie
+ * back to back, 256-byte aligned.  _bytes gives the size of the whole buffer,
+ * _view the byte offset of worker `worker`'s view of `bucket`. */
+typedef struct shadow_device_plan {
+    uint64_t block_bytes;       /* size of the one allocation */
+    uint64_t param_offset;      /* byte offsets inside it, each a multiple of 1 GiB */
+    uint64_t m_offset;
+    uint64_t v_offset;
+    uint64_t scratch_offset;
+    uint64_t staging_offset;
+} shadow_device_plan;
+int32_t shadow_layout_device_plan(const shadow_layout* layout, uint32_t num_workers, int32_t with_scratch,
+                                  int32_t with_staging, shadow_device_plan* plan);
 int32_t shadow_layout_arena_stride(const shadow_layout* layout, uint64_t* stride_bytes);
 int32_t shadow_layout_staging_bytes(const shadow_layout* layout, uint32_t num_workers, uint64_t* bytes);
 int32_t shadow_layout_staging_view(const shadow_layout* layout, uint32_t num_workers, uint32_t bucket,

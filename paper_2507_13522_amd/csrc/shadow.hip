@@ -541,6 +541,40 @@ int32_t shadow_layout_tensor(const shadow_layout* L, uint32_t tensor, uint32_t* 
     return SHADOW_OK;
 }
 
+int32_t shadow_layout_device_plan(const shadow_layout* L, uint32_t num_workers, int32_t with_scratch, int32_t with_staging,
+                                  shadow_device_plan* plan)
+{
+    if (!L || !plan || num_workers < 1 || num_workers > SHADOW_MAX_WORKERS) return SHADOW_EINVAL;
+    constexpr uint64_t kGiB = 1ull << 30, kRegion = 96 * kGiB, kBlock = 256 * kGiB;
+    const uint64_t arena = L->arena_numel * sizeof(float);
+    const uint64_t a = (arena + kGiB - 1) / kGiB * kGiB + kGiB;       // arena rounded up, plus a margin
+    if (2 * a > kRegion) return SHADOW_ENOMEM;
+    shadow_device_plan out{};
+    out.block_bytes = kBlock;
+    out.m_offset = kRegion - a;                 // param and m end the first region
+    out.param_offset = out.m_offset - a;
+    out.v_offset = kRegion + kGiB;              // v starts the second
+    uint64_t tail = out.v_offset + a;
+    if (with_scratch) {
+        if (3 * a <= kRegion) {
+            out.scratch_offset = out.param_offset - a;   // written by the fold: away from the views
+        } else {
+            out.scratch_offset = tail;
+            tail += a;
+        }
+    }
+    if (with_staging) {
+        uint64_t bytes = 0;
+        const int32_t rc = shadow_layout_staging_bytes(L, num_workers, &bytes);
+        if (rc != SHADOW_OK) return rc;
+        out.staging_offset = tail;
+        tail += bytes;
+    }
+    if (tail > kBlock) return SHADOW_ENOMEM;
+    *plan = out;
+    return SHADOW_OK;
+}
+
 int32_t shadow_layout_arena_stride(const shadow_layout* L, uint64_t* stride_bytes)
 {
     if (!L || !stride_bytes) return SHADOW_EINVAL;
@@ -551,11 +585,15 @@ int32_t shadow_layout_arena_stride(const shadow_layout* L, uint64_t* stride_byte
 }
 
 namespace {
+constexpr uint64_t kStagingSkew = 4096;
 uint64_t staging_view_stride(const shadow_layout* L, uint32_t bucket)
 {
     const uint64_t bytes = L->buckets[bucket].numel * L->grad_elem_bytes;
-    const uint64_t a = bytes >= (2ull << 20) ? (2ull << 20) : 256ull;
-    return (bytes + a - 1) / a * a;
+    if (bytes < (2ull << 20)) return (bytes + 255) / 256 * 256;
+    // One page more than a multiple of 2 MiB: the fold reads the same offset of all W views at
+    // the same time, and views a multiple of 2 MiB apart would send those reads to the same
+    // DRAM channel and bank.
+    return (bytes + (2ull << 20) - 1) / (2ull << 20) * (2ull << 20) + kStagingSkew;
 }
 uint64_t staging_bucket_start(const shadow_layout* L, uint32_t num_workers, uint32_t bucket)
 {

@@ -153,6 +153,38 @@ __device__ __forceinline__ void widen_add(const u32x2& a, f32x4& r)
     r[3] = r[3] + bits_to_float(a[1] & 0xFFFF0000u);
 }
 
+// The W views' vectors of one group of 4 elements, as loaded: loading and reducing are
+// separate so that a lane that owns several groups has all its loads in flight at once.
+template <bool BF16>
+struct RawVec { typedef f32x4 type; };
+template <>
+struct RawVec<true> { typedef u32x2 type; };
+
+template <bool BF16, int W>
+__device__ __forceinline__ void load_views4(const void* const* vp, uint64_t vec, typename RawVec<BF16>::type (&raw)[W])
+{
+    typedef typename RawVec<BF16>::type V;
+#pragma unroll
+    for (int w = 0; w < W; ++w) raw[w] = load_once(reinterpret_cast<const V*>(vp[w]) + vec);
+}
+
+template <bool BF16, int W>
+__device__ __forceinline__ f32x4 reduce_views4(const typename RawVec<BF16>::type (&raw)[W], const StepScalars& s)
+{
+    f32x4 r;
+    if constexpr (BF16) {
+        widen_first(raw[0], r);
+#pragma unroll
+        for (int w = 1; w < W; ++w) widen_add(raw[w], r);
+    } else {
+        r = raw[0];
+#pragma unroll
+        for (int w = 1; w < W; ++w) r = r + raw[w];
+    }
+    if (s.mean) r = r * s.inv_w;
+    return r;
+}
+
 template <bool BF16, int W>
 __device__ __forceinline__ f32x4 fold4(const void* const* vp, uint32_t w_rt, uint64_t vec, const StepScalars& s)
 {
@@ -160,11 +192,8 @@ __device__ __forceinline__ f32x4 fold4(const void* const* vp, uint32_t w_rt, uin
     if constexpr (BF16) {
         if constexpr (W > 0) {
             u32x2 raw[W];
-#pragma unroll
-            for (int w = 0; w < W; ++w) raw[w] = load_once(reinterpret_cast<const u32x2*>(vp[w]) + vec);
-            widen_first(raw[0], r);
-#pragma unroll
-            for (int w = 1; w < W; ++w) widen_add(raw[w], r);
+            load_views4<true, W>(vp, vec, raw);
+            return reduce_views4<true, W>(raw, s);
         } else {
             widen_first(load_once(reinterpret_cast<const u32x2*>(vp[0]) + vec), r);
             for (uint32_t w = 1; w < w_rt; ++w) widen_add(load_once(reinterpret_cast<const u32x2*>(vp[w]) + vec), r);
@@ -211,27 +240,46 @@ __device__ __forceinline__ float fold1(const void* const* vp, uint32_t w_rt, uin
     return acc;
 }
 
-// Optimizer step on 4 consecutive arena elements starting at arena element e0 (multiple of 4).
+// State of 4 consecutive arena elements (vector index vec, first element e0 = 4 * vec) and the
+// decay mode of their tile.  Loading, stepping and storing are separate calls so that a kernel
+// can issue every load of a lane, state and gradient views alike, before the first use.
 // SGD has no second moment: v is never touched (it may be null).
+struct State4 {
+    f32x4 p, m, v;
+    uint8_t mode;
+};
+
 template <int OPT>
-__device__ __forceinline__ void update4(float* p, float* m, float* v, uint64_t vec, uint64_t e0, const f32x4& g,
-                                        const WdMap& map, const StepScalars& s)
+__device__ __forceinline__ State4 load_state4(const float* p, const float* m, const float* v, uint64_t vec, uint64_t e0,
+                                              const WdMap& map)
 {
-    f32x4 pp = load_once(reinterpret_cast<const f32x4*>(p) + vec);
-    f32x4 mm = load_once(reinterpret_cast<const f32x4*>(m) + vec);
-    f32x4 vv = {0.f, 0.f, 0.f, 0.f};
-    if constexpr (OPT != kSgd) vv = load_once(reinterpret_cast<const f32x4*>(v) + vec);
-    const uint8_t mode = map.tile_mode[e0 >> kWdTileShift];
+    State4 st;
+    st.p = load_once(reinterpret_cast<const f32x4*>(p) + vec);
+    st.m = load_once(reinterpret_cast<const f32x4*>(m) + vec);
+    st.v = f32x4{0.f, 0.f, 0.f, 0.f};
+    if constexpr (OPT != kSgd) st.v = load_once(reinterpret_cast<const f32x4*>(v) + vec);
+    st.mode = map.tile_mode[e0 >> kWdTileShift];
+    return st;
+}
+
+template <int OPT>
+__device__ __forceinline__ void step_state4(State4& st, uint64_t e0, const f32x4& g, const WdMap& map, const StepScalars& s)
+{
 #pragma unroll
     for (int k = 0; k < kVec; ++k) {
-        const bool flag = (mode != 2) ? (mode != 0) : decay_flag_of(map, e0 + k);
-        float pk = pp[k], mk = mm[k], vk = vv[k];
+        const bool flag = (st.mode != 2) ? (st.mode != 0) : decay_flag_of(map, e0 + k);
+        float pk = st.p[k], mk = st.m[k], vk = st.v[k];
         opt_elem<OPT>(pk, mk, vk, g[k], flag, s);
-        pp[k] = pk; mm[k] = mk; vv[k] = vk;
+        st.p[k] = pk; st.m[k] = mk; st.v[k] = vk;
     }
-    store_once(reinterpret_cast<f32x4*>(p) + vec, pp);
-    store_once(reinterpret_cast<f32x4*>(m) + vec, mm);
-    if constexpr (OPT != kSgd) store_once(reinterpret_cast<f32x4*>(v) + vec, vv);
+}
+
+template <int OPT>
+__device__ __forceinline__ void store_state4(const State4& st, float* p, float* m, float* v, uint64_t vec)
+{
+    store_once(reinterpret_cast<f32x4*>(p) + vec, st.p);
+    store_once(reinterpret_cast<f32x4*>(m) + vec, st.m);
+    if constexpr (OPT != kSgd) store_once(reinterpret_cast<f32x4*>(v) + vec, st.v);
 }
 
 // ---- kernel: fold + AdamW in one pass (clipping off) ---------------------------------
@@ -250,9 +298,15 @@ __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* _
     const uint64_t nvec = n >> 2;
     const uint64_t vec = uint64_t(blockIdx.x - fb.first_block[k]) * blockDim.x + threadIdx.x;
     if (vec < nvec) {
+        float* pb = p + off;
+        float* mb = m + off;
+        float* vb = OPT == kSgd ? nullptr : v + off;
+        const uint64_t e0 = off + (vec << 2);
+        State4 st = load_state4<OPT>(pb, mb, vb, vec, e0, map);   // in flight together with the views
         f32x4 r = fold4<BF16, W>(vp, fb.w, vec, s);
         if (coef) r = r * (*coef);
-        update4<OPT>(p + off, m + off, OPT == kSgd ? nullptr : v + off, vec, off + (vec << 2), r, map, s);
+        step_state4<OPT>(st, e0, r, map, s);
+        store_state4<OPT>(st, pb, mb, vb, vec);
     } else if (vec == nvec) {
         for (uint64_t e = nvec << 2; e < n; ++e) {
             float g = fold1<BF16>(vp, fb.w, e, s);
@@ -283,6 +337,37 @@ constexpr int fold_vpl()
     return v < 1 ? 1 : (v > 8 ? 8 : v);
 }
 
+// Sum of the squares of 4 reduced gradients, added to acc in element order.
+__device__ __forceinline__ void add_squares(const f32x4& g, double& acc)
+{
+#pragma unroll
+    for (int q = 0; q < kVec; ++q) {
+        const double d = double(g[q]);
+        acc = fma(d, d, acc);        // d*d is exact in double, so this equals acc + d*d
+    }
+}
+
+// 8 consecutive bf16 elements per view behind one 128-bit load each; adds in worker order.
+template <int W>
+__device__ __forceinline__ void load_views8_bf16(const void* const* vp, uint64_t vec8, u32x4 (&raw)[W])
+{
+#pragma unroll
+    for (int w = 0; w < W; ++w) raw[w] = load_once(reinterpret_cast<const u32x4*>(vp[w]) + vec8);
+}
+
+template <int W>
+__device__ __forceinline__ void reduce_views8_bf16(const u32x4 (&raw)[W], const StepScalars& s, f32x4& lo, f32x4& hi)
+{
+    widen_first(u32x2{raw[0][0], raw[0][1]}, lo);
+    widen_first(u32x2{raw[0][2], raw[0][3]}, hi);
+#pragma unroll
+    for (int w = 1; w < W; ++w) {
+        widen_add(u32x2{raw[w][0], raw[w][1]}, lo);
+        widen_add(u32x2{raw[w][2], raw[w][3]}, hi);
+    }
+    if (s.mean) { lo = lo * s.inv_w; hi = hi * s.inv_w; }
+}
+
 // r == nullptr: the reduced gradient is not stored (it will be folded again for the update).
 // Every wave writes the sum of its lanes' squares to its own slot, partial[slot_base of the
 // bucket + wave index within the bucket]: no barrier, fixed order.
@@ -297,24 +382,64 @@ __global__ __launch_bounds__(kMaxBlock) void k_fold_sumsq(FoldBatch fb, float* _
     float* r_out = r ? r + fb.arena_off[k] : nullptr;
     const uint64_t nvec = n >> 2;
     const uint32_t local_block = blockIdx.x - fb.first_block[k];
-    const uint64_t base = uint64_t(local_block) * blockDim.x * kVpl + threadIdx.x;
-    f32x4 rr[kVpl];
+    const uint64_t slot = fb.slot_base[k] + uint64_t(local_block) * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    // Few bf16 views and nothing to store (a pure read pass): the lane's groups of 4 elements
+    // are taken in pairs, as 8 consecutive elements behind one 128-bit load per view; the
+    // block covers the same elements, so grid and slots are those of the general path.
+    if constexpr (BF16 && W > 0 && kVpl % 2 == 0) {
+        if (!r_out) {
+            constexpr int kVpl8 = kVpl / 2;
+            const uint64_t nvec8 = n >> 3;
+            const uint64_t base8 = uint64_t(local_block) * blockDim.x * kVpl8 + threadIdx.x;
+            u32x4 raw[kVpl8][W];
 #pragma unroll
-    for (int j = 0; j < kVpl; ++j) {
-        const uint64_t vec = base + uint64_t(j) * blockDim.x;
-        if (vec < nvec) rr[j] = fold4<BF16, W>(vp, fb.w, vec, s);
+            for (int j = 0; j < kVpl8; ++j) {
+                const uint64_t vec8 = base8 + uint64_t(j) * blockDim.x;
+                if (vec8 < nvec8) load_views8_bf16<W>(vp, vec8, raw[j]);
+            }
+            double acc = 0.0;
+#pragma unroll
+            for (int j = 0; j < kVpl8; ++j) {
+                const uint64_t vec8 = base8 + uint64_t(j) * blockDim.x;
+                if (vec8 < nvec8) {
+                    f32x4 lo, hi;
+                    reduce_views8_bf16<W>(raw[j], s, lo, hi);
+                    add_squares(lo, acc);
+                    add_squares(hi, acc);
+                } else if (vec8 == nvec8) {
+                    for (uint64_t e = nvec8 << 3; e < n; ++e) {
+                        const double d = double(fold1<BF16>(vp, fb.w, e, s));
+                        acc = fma(d, d, acc);
+                    }
+                }
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
+            if ((threadIdx.x & 63) == 0) partial[slot] = acc;
+            return;
+        }
+    }
+    const uint64_t base = uint64_t(local_block) * blockDim.x * kVpl + threadIdx.x;
+    // several groups per lane: every group's loads are issued before the first one is reduced
+    constexpr bool kSplit = kVpl > 1;
+    typename RawVec<BF16>::type raw[kSplit ? kVpl : 1][kSplit ? W : 1];
+    if constexpr (kSplit) {
+#pragma unroll
+        for (int j = 0; j < kVpl; ++j) {
+            const uint64_t vec = base + uint64_t(j) * blockDim.x;
+            if (vec < nvec) load_views4<BF16, W>(vp, vec, raw[j]);
+        }
     }
     double acc = 0.0;
 #pragma unroll
     for (int j = 0; j < kVpl; ++j) {
         const uint64_t vec = base + uint64_t(j) * blockDim.x;
         if (vec < nvec) {
-            if (r_out) store_once(reinterpret_cast<f32x4*>(r_out) + vec, rr[j]);
-#pragma unroll
-            for (int q = 0; q < kVec; ++q) {
-                const double d = double(rr[j][q]);
-                acc = fma(d, d, acc);        // d*d is exact in double, so this equals acc + d*d
-            }
+            f32x4 rr;
+            if constexpr (kSplit) rr = reduce_views4<BF16, W>(raw[j], s);
+            else rr = fold4<BF16, W>(vp, fb.w, vec, s);
+            if (r_out) store_once(reinterpret_cast<f32x4*>(r_out) + vec, rr);
+            add_squares(rr, acc);
         } else if (vec == nvec) {
             for (uint64_t e = nvec << 2; e < n; ++e) {
                 const float g = fold1<BF16>(vp, fb.w, e, s);
@@ -326,8 +451,7 @@ __global__ __launch_bounds__(kMaxBlock) void k_fold_sumsq(FoldBatch fb, float* _
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o, 64);
-    if ((threadIdx.x & 63) == 0)
-        partial[fb.slot_base[k] + uint64_t(local_block) * (blockDim.x >> 6) + (threadIdx.x >> 6)] = acc;
+    if ((threadIdx.x & 63) == 0) partial[slot] = acc;
 }
 
 // ---- block-wide sum of doubles in a fixed order ----------------------------------------
@@ -389,8 +513,10 @@ __global__ __launch_bounds__(kMaxBlock) void k_adamw(const float* __restrict__ r
     if (vec >= nvec) return;
     const float c = *coef;
     f32x4 g = load_once(reinterpret_cast<const f32x4*>(r) + vec);
+    State4 st = load_state4<OPT>(p, m, v, vec, vec << 2, map);
     g = g * c;
-    update4<OPT>(p, m, v, vec, vec << 2, g, map, s);
+    step_state4<OPT>(st, vec << 2, g, map, s);
+    store_state4<OPT>(st, p, m, v, vec);
 }
 
 // ---- kernel: plain copy (bandwidth yardstick) ------------------------------------------

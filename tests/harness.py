@@ -153,31 +153,9 @@ def assert_layouts_agree(ol, ll: sh.Layout) -> None:
     assert ll.arena_numel == (prev_end + 63) // 64 * 64
 
 
-GIB = 1 << 30
-DEVICE_BLOCK = 256 * GIB
-HBM_REGION = 96 * GIB
-
-
-def _device_block_plan(arena_bytes: int, staging_bytes: int, narr: int):
-    """Placement of a model-size replica inside one 256 GiB allocation, or None when it does not apply.
-
-    Measured on MI355X (288 GiB of HBM3E): the whole-arena sweep, which reads and writes param, m and v at once, is
-    up to 12 % slower when those three arenas lie in the same third (96 GiB) of the physical memory, and fastest when
-    they are split over two thirds.  A 256 GiB allocation made first in a process is one naturally aligned block of
-    the driver's allocator, so offsets inside it are physical offsets: param and m go to the end of the first third,
-    v and the scratch arena to the start of the second, the staging buffer behind them.
-    """
-    a = (arena_bytes + GIB - 1) // GIB * GIB + GIB          # arena rounded up, plus a 1 GiB margin
-    if arena_bytes < 8 * GIB or 2 * a > HBM_REGION:
-        return None
-    m_off = HBM_REGION - a
-    p_off = m_off - a
-    v_off = HBM_REGION + GIB
-    r_off = v_off + a
-    tail = (r_off + a) if narr == 4 else (v_off + a)
-    if tail + staging_bytes > DEVICE_BLOCK:
-        return None
-    return {"block": DEVICE_BLOCK, "arenas": [p_off, m_off, v_off] + ([r_off] if narr == 4 else []), "staging": tail}
+# Replicas whose arenas reach this size are placed by the library's device plan (one 256 GiB allocation made first
+# thing, arenas and staging buffer at the advised offsets); smaller ones, the parity cases, by its stride advice.
+DEVICE_PLAN_MIN_ARENA_BYTES = 256 << 20
 
 
 class GpuShadow:
@@ -202,15 +180,17 @@ class GpuShadow:
         narr = 4 if (clip and not refold) else 3          # re-fold mode: clipping without a scratch arena
         W = wl.num_workers
         stage_bytes = max(L.staging_bytes(W), 256) if resident_grads else 0
-        plan = _device_block_plan(A * 4, stage_bytes, narr) if advised_placement else None
+        plan = None
+        if advised_placement and A * 4 >= DEVICE_PLAN_MIN_ARENA_BYTES:
+            plan = L.device_plan(W, narr == 4, resident_grads)
         self._stage = None
         if plan is not None:
-            # model-size workloads: ONE 256 GiB allocation, arenas and staging at planned offsets
-            self._state = torch.empty(plan["block"], dtype=torch.uint8, device=self.dev)
-            offs = plan["arenas"]
+            # model-size workloads: ONE 256 GiB allocation, arenas and staging at the planned offsets
+            self._state = torch.empty(plan.block_bytes, dtype=torch.uint8, device=self.dev)
+            offs = [plan.param_offset, plan.m_offset, plan.v_offset] + ([plan.scratch_offset] if narr == 4 else [])
             arenas = [self._state[o:o + A * 4].view(torch.float32) for o in offs]
             if resident_grads:
-                self._stage = self._state[plan["staging"]:plan["staging"] + stage_bytes]
+                self._stage = self._state[plan.staging_offset:plan.staging_offset + stage_bytes]
         else:
             # placement follows the library's advice: the arenas are carved from one allocation, a power-of-two
             # stride apart; the gradient views sit in a bucket-major staging buffer

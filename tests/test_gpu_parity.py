@@ -99,7 +99,7 @@ def test_worker_counts(W, dtype, clip):
     check_against_oracle(wl, num_streams=2)
 
 
-@pytest.mark.parametrize("W,dtype", [(1, "bf16"), (1, "f32"), (3, "bf16"), (8, "bf16"), (64, "f32")])
+@pytest.mark.parametrize("W,dtype", [(1, "bf16"), (2, "bf16"), (4, "bf16"), (1, "f32"), (3, "bf16"), (8, "bf16"), (64, "f32")])
 @pytest.mark.parametrize("batch_bytes", [0, 1 << 62])
 def test_clip_without_scratch_folds_twice(W, dtype, batch_bytes):
     """Clipping with no scratch arena (W = 1 is the paper's case of one already-reduced gradient): the views are

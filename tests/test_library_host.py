@@ -125,7 +125,11 @@ def test_placement_advice():
         n = lay.bucket(b)[1]
         for w in range(W):
             off = lay.staging_view(W, b, w)
-            assert off >= prev_end and off % (2 << 20 if n * 2 >= (2 << 20) else 256) == 0
+            assert off >= prev_end
+            if n * 2 >= (2 << 20):
+                assert off % (2 << 20) == w * 4096             # views of one bucket are skewed by a page each
+            else:
+                assert off % 256 == 0
             prev_end = off + n * 2
     assert prev_end <= total <= 1.03 * lay.num_params * 2 * W    # bucket-major, little padding
     small = sh.Layout([(100, True), (7, False)], 4, 64)
@@ -135,3 +139,37 @@ def test_placement_advice():
         small.staging_view(3, 0, 3)
     with pytest.raises(sh.ShadowError):
         small.staging_view(3, 2, 0)
+
+
+def test_device_plan():
+    """Scratch arena, param and m end the first 96 GiB region, v starts the second, staging follows; nothing overlaps."""
+    G = 1 << 30
+    for name, scratch in (("llama7b", True), ("gpt1p3b", True), ("gpt2s", False), ("llama7b_w1", False)):
+        wl = synth.get_workload(name)
+        lay = lib_layout(wl)
+        W = wl.num_workers
+        plan = lay.device_plan(W, scratch, True)
+        assert plan is not None and plan.block_bytes == 256 * G
+        arena = lay.arena_numel * 4
+        parts = [(plan.param_offset, arena), (plan.m_offset, arena), (plan.v_offset, arena), (plan.staging_offset, lay.staging_bytes(W))]
+        if scratch:
+            parts.append((plan.scratch_offset, arena))
+            assert plan.scratch_offset + arena <= plan.param_offset          # first region, below param
+        else:
+            assert plan.scratch_offset == 0
+        assert plan.param_offset + arena <= plan.m_offset and plan.m_offset + arena <= 96 * G
+        assert plan.v_offset >= 96 * G and plan.staging_offset >= plan.v_offset + arena
+        parts.sort()
+        for (o1, n1), (o2, _) in zip(parts, parts[1:]):
+            assert o1 % G == 0 and o1 + n1 <= o2
+        assert parts[-1][0] + parts[-1][1] <= plan.block_bytes
+    # without a staging buffer the offset is 0; a replica too large for the scheme gets no plan
+    wl = synth.get_workload("llama7b")
+    lay = lib_layout(wl)
+    assert lay.device_plan(8, True, False).staging_offset == 0
+    assert lay.device_plan(32, True, True) is None                            # 32 resident views of 7B: 400 GiB
+    huge = sh.Layout([(13_000_000_000, True)], 4, 1 << 40)
+    assert huge.device_plan(1, False, False) is None                          # two arenas exceed one region
+    L = binding.lib()
+    assert L.shadow_layout_device_plan(None, 1, 0, 0, None) == binding.EINVAL
+
