@@ -24,26 +24,30 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 
-# HBM bytes per launch of the roofline kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
-# (profiles/llama7b_bench_rocprofv3.md), each counter scaled by what it reads for the library's plain copy
-# kernel over 1 GiB.  Only reported while the kernel sources still hash to the value the counters were taken at.
+# HBM bytes per launch of the roofline kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file with
+# its defaults (profiles/*_bench_rocprofv3.md), each counter scaled by what it reads for the library's plain copy
+# kernel over 1 GiB.  Keyed by (workload, kernel, --refold); only reported for default settings and while the
+# kernel sources still hash to the value the counters were taken at.
+MEASURED_TRAFFIC_SOURCES_SHA256 = "7efc8e2dfc37d621e335251e3fefe3bd4f90ba4d464560af93ce6f675fe710a0"
 MEASURED_TRAFFIC = {
-    ("llama7b", "k_adamw"): {"bytes_per_launch": 188703744975.6,
-                             "sources_sha256": "924245fa3bea98c8c3a57f1c3718bf8d18257a559bfe9316657ee44595e28de9"},
+    ("llama7b", "k_adamw", False): 188700968649.7,
+    ("gpt1p3b", "k_fold_sumsq", False): 4740577865.2,
+    ("llama7b_w1", "k_fold_adamw", True): 21903530156.9,
+    ("gpt2s", "k_fold_adamw", False): 4978293592.9,
 }
 KERNEL_SOURCES = ("paper_2507_13522_amd/csrc/shadow_kernels.hip.h", "paper_2507_13522_amd/csrc/shadow.hip")
 
 
-def measured_traffic(workload: str, kernel: str):
+def measured_traffic(workload: str, kernel: str, refold: bool, defaults: bool):
     import hashlib
-    rec = MEASURED_TRAFFIC.get((workload, kernel))
-    if rec is None:
+    rec = MEASURED_TRAFFIC.get((workload, kernel, refold))
+    if rec is None or not defaults:
         return None
     h = hashlib.sha256()
     for f in KERNEL_SOURCES:
         with open(os.path.join(ROOT, f), "rb") as fh:
             h.update(fh.read())
-    return rec["bytes_per_launch"] if h.hexdigest() == rec["sources_sha256"] else None
+    return rec if h.hexdigest() == MEASURED_TRAFFIC_SOURCES_SHA256 else None
 
 
 KERNEL_NAMES = {0: "k_fold_adamw", 1: "k_fold_sumsq", 2: "k_norm_finalize", 3: "k_adamw"}
@@ -142,6 +146,9 @@ def main() -> int:
     from harness import BENCH_BATCH_BYTES, BENCH_STREAMS, GpuShadow, Inputs, TILE_PERIOD
     streams = BENCH_STREAMS if args.streams is None else args.streams
     batch_bytes = BENCH_BATCH_BYTES if args.batch_mib is None else args.batch_mib << 20
+
+    default_settings = (args.streams is None and args.batch_mib is None and args.optimizer == "adamw" and not args.ingest_slots
+                        and not args.fold_block and not args.adamw_block)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -257,7 +264,7 @@ def main() -> int:
         "hbm_frac_of_copy_kernel": (total_gbs / yard) if yard else None,
         "kernels": kernels,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name, dom),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name, dom, bool(args.refold), default_settings),
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": kernels[dom]["avg_ms"]},
     }
     g.close()
