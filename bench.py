@@ -90,25 +90,47 @@ def cpu_baseline(wl, inputs, target_seconds: float = 15.0, optimizer: str = "ada
                        p=inputs.param_np(starts[b], n), m=np.zeros(n, np.float32), v=np.zeros(n, np.float32))
     params = [data[b]["p"] if b in data else None for b in range(len(lay.buckets))]
     orc = oracle.OracleShadow(lay, hp, params)
-    done, t_used, t = 0, 0.0, 0
-    while t_used < target_seconds and t < 200:
-        t += 1
-        t0 = time.perf_counter()
-        r = {b: oracle.fold(data[b]["g"], hp.mean) for b in chosen}
-        c = None
-        if hp.max_grad_norm > 0:
-            s = oracle.SumSq()
+    t = 0
+
+    def timed(budget: float, max_iters: int):
+        nonlocal t
+        done, t_used, iters = 0, 0.0, 0
+        while t_used < budget and iters < max_iters:
+            t += 1
+            iters += 1
+            t0 = time.perf_counter()
+            r = {b: oracle.fold(data[b]["g"], hp.mean) for b in chosen}
+            c = None
+            if hp.max_grad_norm > 0:
+                s = oracle.SumSq()
+                for b in chosen:
+                    s.add(r[b])
+                c = s.coef(hp.max_grad_norm)
             for b in chosen:
-                s.add(r[b])
-            c = s.coef(hp.max_grad_norm)
-        for b in chosen:
-            orc.update_bucket(b, r[b], t, c)
-        t_used += time.perf_counter() - t0
-        done += total
-    return {"value": done / t_used, "unit": "params/s", "cores": threads, "kind": "oracle",
-            "sample": f"{len(chosen)} buckets ({total} params) of {wl.name}, {t} oracle iterations "
+                orc.update_bucket(b, r[b], t, c)
+            t_used += time.perf_counter() - t0
+            done += total
+        return done / t_used, iters, t_used
+
+    rate, iters, t_used = timed(target_seconds, 200)
+    # the same loop on one thread, a third of the budget
+    oracle.set_threads(1)
+    try:
+        rate1, iters1, t_used1 = timed(target_seconds / 3, 50)
+    finally:
+        oracle.set_threads(threads)
+    cpu = "unknown"
+    try:
+        with open("/proc/cpuinfo") as fh:
+            cpu = next((ln.split(":", 1)[1].strip() for ln in fh if ln.startswith("model name")), cpu)
+    except OSError:
+        pass
+    return {"value": rate, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "sample": f"{len(chosen)} buckets ({total} params) of {wl.name}, {iters} oracle iterations "
                       f"(fold W={wl.num_workers} {wl.grad_dtype}, norm, {optimizer}), {t_used:.1f} s of CPU work, "
-                      f"OpenMP threads={threads}, host cpus={os.cpu_count()}"}
+                      f"OpenMP threads={threads}, host cpus={os.cpu_count()}, cpu={cpu}",
+            "value_single_thread": rate1,
+            "sample_single_thread": f"same buckets, {iters1} iterations, {t_used1:.1f} s on one thread"}
 
 
 def main() -> int:
