@@ -135,8 +135,10 @@ int32_t shadow_layout_tensor(const shadow_layout* layout, uint32_t tensor, uint3
  * (256 GiB).  Made first in a process, such an allocation is one naturally
  * aligned block of the driver's allocator, so offsets inside it are physical
  * offsets: the scratch arena, param and m end the first region, v starts the
- * second, the staging buffer follows v.  with_scratch / with_staging: nonzero
- * when the caller wants those parts (their offsets are 0 otherwise).
+ * second, the staging buffer follows v.  with_scratch: nonzero when the caller
+ * wants a scratch arena; staging_bytes: size of the gradient buffer the caller
+ * wants placed (the whole bucket-major buffer of shadow_layout_staging_bytes,
+ * or a ring of its own size), 0 for none.  Offsets of absent parts are 0.
  * SHADOW_ENOMEM when the parts do not fit this scheme (the caller then places
  * them itself, e.g. by the stride below).
  *
@@ -159,8 +161,8 @@ typedef struct shadow_device_plan {
     uint64_t scratch_offset;
     uint64_t staging_offset;
 } shadow_device_plan;
-int32_t shadow_layout_device_plan(const shadow_layout* layout, uint32_t num_workers, int32_t with_scratch,
-                                  int32_t with_staging, shadow_device_plan* plan);
+int32_t shadow_layout_device_plan(const shadow_layout* layout, int32_t with_scratch, uint64_t staging_bytes,
+                                  shadow_device_plan* plan);
 int32_t shadow_layout_arena_stride(const shadow_layout* layout, uint64_t* stride_bytes);
 int32_t shadow_layout_staging_bytes(const shadow_layout* layout, uint32_t num_workers, uint64_t* bytes);
 int32_t shadow_layout_staging_view(const shadow_layout* layout, uint32_t num_workers, uint32_t bucket,

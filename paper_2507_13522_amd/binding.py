@@ -56,7 +56,7 @@ _SIGS = {
     "shadow_layout_arena_numel": [C.c_void_p, C.POINTER(C.c_uint64)],
     "shadow_layout_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)],
     "shadow_layout_tensor": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)],
-    "shadow_layout_device_plan": [C.c_void_p, C.c_uint32, C.c_int32, C.c_int32, C.POINTER(DevicePlan)],
+    "shadow_layout_device_plan": [C.c_void_p, C.c_int32, C.c_uint64, C.POINTER(DevicePlan)],
     "shadow_layout_arena_stride": [C.c_void_p, C.POINTER(C.c_uint64)],
     "shadow_layout_staging_bytes": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64)],
     "shadow_layout_staging_view": [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64)],
@@ -154,10 +154,11 @@ class Layout:
         _check(lib().shadow_layout_tensor(self._h, t, C.byref(b), C.byref(ob), C.byref(oa)), "shadow_layout_tensor")
         return b.value, ob.value, oa.value
 
-    def device_plan(self, num_workers: int, with_scratch: bool, with_staging: bool) -> Optional[DevicePlan]:
-        """Offsets of the arenas and the staging buffer inside one 256 GiB allocation, or None when they do not fit."""
+    def device_plan(self, with_scratch: bool, staging_bytes: int) -> Optional[DevicePlan]:
+        """Offsets of the arenas and of a gradient buffer of staging_bytes (0: none) inside one 256 GiB allocation,
+        or None when they do not fit."""
         plan = DevicePlan()
-        rc = lib().shadow_layout_device_plan(self._h, num_workers, int(with_scratch), int(with_staging), C.byref(plan))
+        rc = lib().shadow_layout_device_plan(self._h, int(with_scratch), staging_bytes, C.byref(plan))
         if rc == ENOMEM:
             return None
         _check(rc, "shadow_layout_device_plan")

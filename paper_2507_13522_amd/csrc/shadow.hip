@@ -541,10 +541,9 @@ int32_t shadow_layout_tensor(const shadow_layout* L, uint32_t tensor, uint32_t* 
     return SHADOW_OK;
 }
 
-int32_t shadow_layout_device_plan(const shadow_layout* L, uint32_t num_workers, int32_t with_scratch, int32_t with_staging,
-                                  shadow_device_plan* plan)
+int32_t shadow_layout_device_plan(const shadow_layout* L, int32_t with_scratch, uint64_t staging_bytes, shadow_device_plan* plan)
 {
-    if (!L || !plan || num_workers < 1 || num_workers > SHADOW_MAX_WORKERS) return SHADOW_EINVAL;
+    if (!L || !plan) return SHADOW_EINVAL;
     constexpr uint64_t kGiB = 1ull << 30, kRegion = 96 * kGiB, kBlock = 256 * kGiB;
     const uint64_t arena = L->arena_numel * sizeof(float);
     const uint64_t a = (arena + kGiB - 1) / kGiB * kGiB + kGiB;       // arena rounded up, plus a margin
@@ -563,12 +562,10 @@ int32_t shadow_layout_device_plan(const shadow_layout* L, uint32_t num_workers, 
             tail += a;
         }
     }
-    if (with_staging) {
-        uint64_t bytes = 0;
-        const int32_t rc = shadow_layout_staging_bytes(L, num_workers, &bytes);
-        if (rc != SHADOW_OK) return rc;
+    if (staging_bytes) {
+        if (staging_bytes > kBlock) return SHADOW_ENOMEM;
         out.staging_offset = tail;
-        tail += bytes;
+        tail += staging_bytes;
     }
     if (tail > kBlock) return SHADOW_ENOMEM;
     *plan = out;

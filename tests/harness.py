@@ -163,7 +163,8 @@ class GpuShadow:
 
     def __init__(self, wl: synth.Workload, inputs: Inputs, num_streams: int = 2, mean: bool = True,
                  torch_streams: bool = False, resident_grads: bool = True, init_from=None, start_step: int = 0,
-                 advised_placement: bool = True, batch_bytes: int = 0, refold: bool = False, optimizer: str = "adamw"):
+                 advised_placement: bool = True, batch_bytes: int = 0, refold: bool = False, optimizer: str = "adamw",
+                 ring_bytes: int = 0):
         assert torch.cuda.is_available()
         self.wl, self.inputs = wl, inputs
         self.dev = torch.device("cuda:0")
@@ -180,9 +181,23 @@ class GpuShadow:
         narr = 4 if (clip and not refold) else 3          # re-fold mode: clipping without a scratch arena
         W = wl.num_workers
         stage_bytes = max(L.staging_bytes(W), 256) if resident_grads else 0
+        # ring_bytes > 0 (timing only): the views do not all fit, so bucket after bucket takes the next piece of a
+        # ring of that size and later buckets reuse the memory of earlier ones; contents are then meaningless
+        self._ring_off = None
+        if resident_grads and ring_bytes:
+            self._ring_off, cur = [], 0
+            for b in range(L.num_buckets):
+                need = (L.staging_view(W, b, W - 1) - L.staging_view(W, b, 0)) + self.buckets[b][1] * wl.grad_bytes
+                need = (need + (2 << 20) - 1) // (2 << 20) * (2 << 20)
+                assert need <= ring_bytes, "ring smaller than one bucket's views"
+                if cur + need > ring_bytes:
+                    cur = 0
+                self._ring_off.append(cur)
+                cur += need
+            stage_bytes = ring_bytes
         plan = None
         if advised_placement and A * 4 >= DEVICE_PLAN_MIN_ARENA_BYTES:
-            plan = L.device_plan(W, narr == 4, resident_grads)
+            plan = L.device_plan(narr == 4, stage_bytes)
         self._stage = None
         if plan is not None:
             # model-size workloads: ONE 256 GiB allocation, arenas and staging at the planned offsets
@@ -225,7 +240,10 @@ class GpuShadow:
     def view(self, b: int, w: int) -> torch.Tensor:
         """Worker w's gradient view of bucket b inside the staging buffer."""
         n = self.buckets[b][1]
-        off = self.layout.staging_view(self.wl.num_workers, b, w)
+        W = self.wl.num_workers
+        off = self.layout.staging_view(W, b, w)
+        if self._ring_off is not None:
+            off = self._ring_off[b] + off - self.layout.staging_view(W, b, 0)
         return self._stage[off:off + n * self.wl.grad_bytes].view(self.gdt)
 
     def fill_grads(self, step: int, buckets: Optional[Sequence[int]] = None) -> None:

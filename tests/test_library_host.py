@@ -148,7 +148,7 @@ def test_device_plan():
         wl = synth.get_workload(name)
         lay = lib_layout(wl)
         W = wl.num_workers
-        plan = lay.device_plan(W, scratch, True)
+        plan = lay.device_plan(scratch, lay.staging_bytes(W))
         assert plan is not None and plan.block_bytes == 256 * G
         arena = lay.arena_numel * 4
         parts = [(plan.param_offset, arena), (plan.m_offset, arena), (plan.v_offset, arena), (plan.staging_offset, lay.staging_bytes(W))]
@@ -166,10 +166,12 @@ def test_device_plan():
     # without a staging buffer the offset is 0; a replica too large for the scheme gets no plan
     wl = synth.get_workload("llama7b")
     lay = lib_layout(wl)
-    assert lay.device_plan(8, True, False).staging_offset == 0
-    assert lay.device_plan(32, True, True) is None                            # 32 resident views of 7B: 400 GiB
+    assert lay.device_plan(True, 0).staging_offset == 0
+    assert lay.device_plan(True, lay.staging_bytes(32)) is None                # 32 resident views of 7B: 400 GiB
+    ring = lay.device_plan(True, 100 << 30)                                   # a 100 GiB ring instead
+    assert ring is not None and ring.staging_offset + (100 << 30) <= ring.block_bytes
     huge = sh.Layout([(13_000_000_000, True)], 4, 1 << 40)
-    assert huge.device_plan(1, False, False) is None                          # two arenas exceed one region
+    assert huge.device_plan(False, 0) is None                          # two arenas exceed one region
     L = binding.lib()
-    assert L.shadow_layout_device_plan(None, 1, 0, 0, None) == binding.EINVAL
+    assert L.shadow_layout_device_plan(None, 0, 0, None) == binding.EINVAL
 
