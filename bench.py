@@ -249,17 +249,27 @@ def main() -> int:
         yard = 5 * 2 * nb / (e0.elapsed_time(e1) * 1e-3) / 1e9
         del src, dst
     torch.cuda.synchronize()
+    # per-step marks on the library's own stream (single-stream runs): no host synchronisation inside the timed region
+    marks, mark_stream = None, None
+    if streams == 1 and not ingest:
+        mark_stream = torch.cuda.ExternalStream(g.ctx.bucket_stream(0))
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     g.ctx.profile_enable(True)
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    if marks:
+        marks[0].record(mark_stream)
+    for i in range(args.steps):
         step += 1
         run_step(step)
+        if marks:
+            marks[i + 1].record(mark_stream)
     g.ctx.sync()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     g.ctx.profile_enable(False)
 
     ms_per_step = 1e3 * elapsed / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)) if marks else None
     bpp = algorithmic_bytes_per_param(wl, args.refold, args.optimizer)
     kernels = {}
     for kind, name in KERNEL_NAMES.items():
@@ -284,6 +294,9 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_median": (per_step[len(per_step) // 2] if len(per_step) % 2 else
+                               0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])) if per_step else None,
+        "ms_per_step_min": per_step[0] if per_step else None,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
