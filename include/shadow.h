@@ -22,6 +22,9 @@
  *     gradient views are BORROWED.  It allocates only small device tables
  *     (weight-decay map, norm partials) that it owns.
  *   - Calls on one context are not thread-safe; use one host thread per context.
+ *   - The calls record and wait on events, keep host-side bookkeeping per
+ *     iteration and pass per-iteration scalars as kernel arguments: do not
+ *     issue them while a stream is being captured into a HIP graph.
  */
 #ifndef SHADOW_H
 #define SHADOW_H
