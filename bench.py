@@ -18,9 +18,8 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-for p in (ROOT, os.path.join(ROOT, "tests")):
-    if p not in sys.path:
-        sys.path.insert(0, p)
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 
@@ -73,11 +72,12 @@ def cpu_baseline(wl, inputs, target_seconds: float = 15.0, optimizer: str = "ada
     """Time the oracle, as it stands, on this machine's host cores over a bounded sample of the same workload."""
     import numpy as np
     import oracle
-    from harness import oracle_hparams, oracle_layout
 
-    lay = oracle_layout(wl)
+    lay = oracle.build_layout([(t.numel, t.weight_decay) for t in wl.tensors], wl.grad_bytes, wl.bucket_cap_bytes,
+                              wl.explicit_buckets)
     starts = lay.logical_starts()
-    hp = oracle_hparams(wl, optimizer=optimizer)
+    hp = oracle.HParams(lr=wl.lr, beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, weight_decay=wl.weight_decay,
+                        max_grad_norm=wl.max_grad_norm, mean=True, optimizer=optimizer)
     threads = oracle.get_threads()
     # sample: buckets in id order until ~64M elements (bounded host memory), repeated until the time budget is used
     chosen, total = [], 0
@@ -155,7 +155,21 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-yardstick", action="store_true", help="skip timing the plain copy kernel")
     ap.add_argument("--fold-block", type=int, default=0)
-    ap.add_argument("--adamw-block", type=int, default=0)
+    ap.add_argument("--sweep-block", type=int, default=0)
+    ap.add_argument("--fold-waves", type=int, default=0, help="upper bound on the waves per CU of the per-bucket kernels")
+    ap.add_argument("--sweep-waves", type=int, default=0, help="upper bound on the waves per CU of the optimizer sweep")
+    ap.add_argument("--placement", default="auto", choices=["auto", "plan", "stride", "separate"],
+                    help="where the arenas and views lie in HBM (auto: the library's device plan, else its stride advice)")
+    ap.add_argument("--snapshot-every", type=int, default=0,
+                    help="take a snapshot of the replica every N-th timed iteration (0 = never)")
+    ap.add_argument("--snapshot-mode", default="staged", choices=["staged", "copy"],
+                    help="staged: the iteration's update also writes a staging set (shadow_snapshot_arm); "
+                         "copy: device-to-device copies at the boundary (shadow_snapshot)")
+    ap.add_argument("--snapshot-host", action="store_true",
+                    help="drain every snapshot to pinned host memory (staged: from the staging set, concurrently with "
+                         "later iterations; copy: straight from the replica)")
+    ap.add_argument("--view-ring-gib", type=int, default=0,
+                    help="let the buckets' views take turns in a ring of this many GiB instead of keeping all resident")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch the library's plain copy kernel once over this many MiB (known-traffic "
                          "yardstick for rocprofv3 byte counters)")
@@ -168,38 +182,65 @@ def main() -> int:
     import torch
     import paper_2507_13522_amd as sh
     import synth
-    from harness import BENCH_BATCH_BYTES, BENCH_STREAMS, GpuShadow, Inputs, TILE_PERIOD
+    from paper_2507_13522_amd.replica import BENCH_BATCH_BYTES, BENCH_STREAMS, GpuShadow
+    from synth.inputs import TILE_PERIOD, Inputs
     streams = BENCH_STREAMS if args.streams is None else args.streams
     batch_bytes = BENCH_BATCH_BYTES if args.batch_mib is None else args.batch_mib << 20
 
     default_settings = (args.streams is None and args.batch_mib is None and args.optimizer == "adamw" and not args.ingest_slots
-                        and not args.fold_block and not args.adamw_block)
+                        and not args.fold_block and not args.sweep_block and not args.fold_waves and not args.sweep_waves
+                        and args.placement == "auto" and not args.snapshot_every and not args.view_ring_gib)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
-    if args.fold_block:
-        sh.shadow_set_tunable("fold_block", args.fold_block)
-    if args.adamw_block:
-        sh.shadow_set_tunable("adamw_block", args.adamw_block)
+    launch = sh.LaunchShape(fold_block=args.fold_block, sweep_block=args.sweep_block, fold_waves_per_cu=args.fold_waves,
+                            sweep_waves_per_cu=args.sweep_waves)
 
     wl = synth.get_workload(args.workload)
     inputs = Inputs(wl, period=TILE_PERIOD)
     ingest = args.ingest_slots > 0
     # all W views of every bucket resident when they fit beside the replica; otherwise (W = 32 at 7B: 445 GB) the
     # buckets take turns in a ring of views, which moves the same bytes per step (values do not affect timing)
-    ring_bytes = 0
-    if not ingest:
-        from harness import lib_layout
-        lay = lib_layout(wl)
-        scratch = wl.max_grad_norm > 0 and not args.refold
-        if lay.arena_numel * 16 + lay.staging_bytes(wl.num_workers) > (250 << 30):
-            ring_bytes = VIEW_RING_BYTES
-            assert lay.device_plan(scratch, ring_bytes) is not None
+    ring_bytes = args.view_ring_gib << 30
+    snapshots = args.snapshot_every > 0
+    staged = snapshots and args.snapshot_mode == "staged"
+    if not ingest and not ring_bytes:
+        lay = sh.Layout([(t.numel, t.weight_decay) for t in wl.tensors], wl.grad_bytes, wl.bucket_cap_bytes, wl.explicit_buckets)
+        state_bytes = lay.arena_numel * (16 + (12 if snapshots else 0))
+        if state_bytes + lay.staging_bytes(wl.num_workers) > (250 << 30):
+            ring_bytes = VIEW_RING_BYTES if not snapshots else 32 << 30
         lay.close()
     g = GpuShadow(wl, inputs, num_streams=streams, batch_bytes=batch_bytes, refold=args.refold, optimizer=args.optimizer,
-                  resident_grads=not ingest, ring_bytes=ring_bytes)
+                  resident_grads=not ingest, ring_bytes=ring_bytes, placement=args.placement, snapshot_set=staged, launch=launch)
     P = g.layout.num_params
+    A = g.layout.arena_numel
+    snap_dev = snap_host = None
+    if snapshots and args.snapshot_host:
+        snap_host = [torch.empty(A, dtype=torch.float32).pin_memory() for _ in range(3)]
+    elif snapshots and not staged:
+        snap_dev = [torch.empty(A, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    snap_taken, snap_skipped = 0, 0
+
+    def before_step(i):
+        """staged snapshots are armed before the iteration whose end state they hold"""
+        nonlocal snap_taken, snap_skipped
+        if staged and (i + 1) % args.snapshot_every == 0:
+            rc = g.ctx.try_snapshot_arm(*([h.data_ptr() for h in snap_host] if snap_host else [None, None, None]))
+            if rc == sh.binding.OK:
+                snap_taken += 1
+            elif rc == sh.binding.EBUSY:
+                snap_skipped += 1          # the previous drain to the host is still running
+            else:
+                raise sh.ShadowError(rc, "shadow_snapshot_arm")
+
+    def after_step(i):
+        nonlocal snap_taken
+        if snapshots and not staged and (i + 1) % args.snapshot_every == 0:
+            dst = snap_host if snap_host else snap_dev
+            g.ctx.snapshot(*(d.data_ptr() for d in dst))
+            snap_taken += 1
+
     if ingest:
         # one pinned host buffer per worker, as long as the largest bucket, serves every bucket (values do not
         # affect timing); the device ring holds ingest_slots buckets
@@ -260,9 +301,17 @@ def main() -> int:
         marks[0].record(mark_stream)
     for i in range(args.steps):
         step += 1
+        before_step(i)
         run_step(step)
+        after_step(i)
         if marks:
             marks[i + 1].record(mark_stream)
+    t_updates = None
+    if snapshots:
+        # the updates are done when the library's compute streams are; a drain to the host may still be running
+        for b in range(min(streams, len(g.buckets))):
+            torch.cuda.ExternalStream(g.ctx.bucket_stream(b)).synchronize()
+        t_updates = time.perf_counter() - t0
     g.ctx.sync()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -286,6 +335,12 @@ def main() -> int:
     achieved = bytes_per_launch / (kernels[dom]["avg_ms"] * 1e-3) / 1e9
     total_gbs = bpp["total"] * P / (ms_per_step * 1e-3) / 1e9
 
+    traffic = measured_traffic(wl.name, dom, bool(args.refold), default_settings and g.placement == "plan")
+    traffic_source = None
+    if traffic is not None:
+        traffic_source = (f"stored, not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, "
+                          f"profiles/{wl.name}{'_refold' if args.refold else ''}_bench_rocprofv3.md, "
+                          f"taken at kernel sources sha256 {MEASURED_TRAFFIC_SOURCES_SHA256[:16]}")
     out = {
         "metric": "shadow update params/sec and achieved HBM GB/s (% of peak) per iteration",
         "value": P / (ms_per_step * 1e-3),
@@ -308,7 +363,9 @@ def main() -> int:
                    "num_params": P, "num_buckets": len(g.buckets), "num_workers": wl.num_workers,
                    "grad_dtype": wl.grad_dtype, "streams": streams,
                    "batch_bytes": batch_bytes, "refold": bool(args.refold), "optimizer": args.optimizer,
-                   "ingest_slots": args.ingest_slots, "view_ring_bytes": ring_bytes},
+                   "ingest_slots": args.ingest_slots, "view_ring_bytes": ring_bytes, "placement": g.placement,
+                   "snapshot_every": args.snapshot_every, "snapshot_mode": args.snapshot_mode if snapshots else None,
+                   "snapshot_to_host": bool(snapshots and args.snapshot_host)},
         "hbm_GBps": total_gbs,
         "hbm_frac_of_peak": total_gbs / HBM_PEAK_GBS,
         "bytes_per_param": bpp["total"],
@@ -316,9 +373,13 @@ def main() -> int:
         "hbm_frac_of_copy_kernel": (total_gbs / yard) if yard else None,
         "kernels": kernels,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(wl.name, dom, bool(args.refold), default_settings),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": kernels[dom]["avg_ms"]},
     }
+    if snapshots:
+        out["snapshots"] = {"taken": snap_taken, "skipped_while_draining": snap_skipped,
+                            "ms_per_step_updates_only": 1e3 * t_updates / args.steps,
+                            "extra_bytes_per_param_on_a_snapshot_step": 12 if staged else 24}
     g.close()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, inputs, optimizer=args.optimizer)

@@ -25,6 +25,10 @@
  *   - The calls record and wait on events, keep host-side bookkeeping per
  *     iteration and pass per-iteration scalars as kernel arguments: do not
  *     issue them while a stream is being captured into a HIP graph.
+ *   - Events and streams cross the boundary as void* holding a hipEvent_t /
+ *     hipStream_t of the caller's HIP runtime.
+ *   - Measurement aids (per-kernel timing, a copy kernel of known traffic) are
+ *     declared in shadow_measure.h; they are not part of the method.
  */
 #ifndef SHADOW_H
 #define SHADOW_H
@@ -63,6 +67,25 @@ typedef struct {
     uint32_t reserved;      /* must be 0                                               */
 } shadow_tensor_desc;
 
+/* Launch shape of the kernels of ONE replica (part of shadow_hparams; every field 0 = the
+ * library's default, which is what was measured fastest on MI355X).  Results never depend on it.
+ *   fold_block, sweep_block   threads per block of the per-bucket kernels (default 1024) and of
+ *                             the whole-arena optimizer sweep (default 256): 64, 128, 256, 512 or 1024.
+ *   fold_waves_per_cu, sweep_waves_per_cu   upper bound on the waves a compute unit holds at a
+ *                             time, 1..32 (32 = no bound; defaults: 32 and 16).  Fewer requests in
+ *                             flight keep DRAM rows open longer; enforced by reserving unused LDS.
+ *   max_launch_threads        a logical launch with more threads is issued as several launches
+ *                             (default and upper limit 2^31; lower values exist so that tests can
+ *                             reach the split paths with small inputs; at least one block and one
+ *                             bucket go into every launch). */
+typedef struct {
+    uint32_t fold_block;
+    uint32_t sweep_block;
+    uint32_t fold_waves_per_cu;
+    uint32_t sweep_waves_per_cu;
+    uint64_t max_launch_threads;
+} shadow_launch_shape;
+
 /* Optimizer and reduce settings (AdamW: section 6; reduce: section 2.1). */
 typedef struct {
     float    lr;             /* >= 0                                                       */
@@ -83,6 +106,7 @@ typedef struct {
                                 0 = launch every bucket at once (lowest latency); a large value =
                                 fewest launches (a 50 MiB bucket is only ~90 us of HBM time, so launch
                                 ramps and gaps cost ~4 % of the fold when every bucket is its own launch) */
+    shadow_launch_shape launch;  /* all zero = the library's defaults                          */
 } shadow_hparams;
 
 /* ------------------------------------------------------------------------ *
@@ -133,13 +157,14 @@ int32_t shadow_layout_tensor(const shadow_layout* layout, uint32_t tensor, uint3
  * another).  The W views of one bucket stream best close together
  * (bucket-major: 6.4 TB/s, one arena-sized buffer per worker: 6.05 TB/s).
  *
- * shadow_layout_device_plan: byte offsets for param, m, v, the scratch arena
- * and the staging buffer inside ONE device allocation of block_bytes
- * (256 GiB).  Made first in a process, such an allocation is one naturally
+ * shadow_layout_device_plan: byte offsets for param, m, v, the scratch arena,
+ * a snapshot staging set (shadow_snapshot_attach) and the staging buffer of the
+ * gradient views inside ONE device allocation of block_bytes (256 GiB).  Made first in a process, such an allocation is one naturally
  * aligned block of the driver's allocator, so offsets inside it are physical
  * offsets: the scratch arena, param and m end the first region, v starts the
- * second, the staging buffer follows v.  with_scratch: nonzero when the caller
- * wants a scratch arena; staging_bytes: size of the gradient buffer the caller
+ * second, the snapshot set follows v and the staging buffer comes last.
+ * with_scratch / with_snapshot_set: nonzero when the caller wants a scratch
+ * arena / a second set of param, m, v arenas; staging_bytes: size of the gradient buffer the caller
  * wants placed (the whole bucket-major buffer of shadow_layout_staging_bytes,
  * or a ring of its own size), 0 for none.  Offsets of absent parts are 0.
  * SHADOW_ENOMEM when the parts do not fit this scheme (the caller then places
@@ -163,9 +188,12 @@ typedef struct shadow_device_plan {
     uint64_t v_offset;
     uint64_t scratch_offset;
     uint64_t staging_offset;
+    uint64_t snap_param_offset; /* snapshot staging set; 0 when not asked for */
+    uint64_t snap_m_offset;
+    uint64_t snap_v_offset;
 } shadow_device_plan;
-int32_t shadow_layout_device_plan(const shadow_layout* layout, int32_t with_scratch, uint64_t staging_bytes,
-                                  shadow_device_plan* plan);
+int32_t shadow_layout_device_plan(const shadow_layout* layout, int32_t with_scratch, int32_t with_snapshot_set,
+                                  uint64_t staging_bytes, shadow_device_plan* plan);
 int32_t shadow_layout_arena_stride(const shadow_layout* layout, uint64_t* stride_bytes);
 int32_t shadow_layout_staging_bytes(const shadow_layout* layout, uint32_t num_workers, uint64_t* bytes);
 int32_t shadow_layout_staging_view(const shadow_layout* layout, uint32_t num_workers, uint32_t bucket,
@@ -176,7 +204,9 @@ int32_t shadow_layout_staging_view(const shadow_layout* layout, uint32_t num_wor
  * ------------------------------------------------------------------------ */
 typedef struct shadow_ctx shadow_ctx;
 
-/* Create a replica over caller-allocated arenas on the current HIP device.
+/* Create a replica over caller-allocated arenas on the current HIP device: the
+ * shadow's copy of the training state, i.e. the parameters and the optimizer's
+ * state (section 2.1), which starts out equal to the trainers' (section 4.2.3).
  *   layout     host object, copied (may be destroyed afterwards).
  *   hp         host pointer.
  *   d_param, d_m, d_v   device pointers, arena_numel floats each, 256-byte
@@ -196,36 +226,65 @@ typedef struct shadow_ctx shadow_ctx;
  *              gradient per bucket, W = 1); the views of the whole iteration
  *              must then stay unchanged until its update has run.
  *   start_step iterations already applied to this state (0 for a fresh
- *              replica; a snapshot's step when restoring).  The first
- *              iteration applied is start_step + 1; Adam's bias correction
- *              uses that 1-based count.
+ *              replica; a snapshot's step when restoring: section 6.5 resumes
+ *              training from the shadow's checkpoint).  The first iteration
+ *              applied is start_step + 1; Adam's bias correction uses that
+ *              1-based count.
  *   streams    host array of hp->num_streams hipStream_t handles (for example
  *              torch streams' .cuda_stream), borrowed; or NULL: the library
  *              creates and owns default-priority streams.
+ * Errors: EINVAL (null or misaligned arena, bad hyper-parameter, a bucket too
+ * large for one launch), ENOMEM, EHIP; nothing is left allocated on an error.
  */
 int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_hparams* hp,
                     float* d_param, float* d_m, float* d_v, float* d_reduced,
                     uint64_t start_step, void* const* streams);
 
-/* Apply one bucket of iteration `step`: fold the W gradient views and (when
- * clipping is off) update the bucket's parameters in the same kernel; when
- * clipping is on the fold stores the reduced gradient and its sum of squares,
- * and the call that delivers the last missing bucket of the iteration also
- * enqueues the norm and the update of every bucket.
+/* The replica's bucket map (section 4.2.2: the shadow keeps the mapping from
+ * buckets to parameter offsets).  Same numbers as shadow_layout_num_buckets /
+ * shadow_layout_bucket on the layout the replica was created from; they exist
+ * on the context because the layout object need not outlive shadow_init. */
+int32_t shadow_num_buckets(const shadow_ctx* ctx, uint32_t* out);
+int32_t shadow_bucket_info(const shadow_ctx* ctx, uint32_t bucket_id, uint64_t* arena_offset, uint64_t* numel);
+
+/* Apply one bucket of iteration `step` (section 4.2.3: the shadow receives
+ * the gradient buckets of an iteration and runs the trainers' optimizer step;
+ * section 4.2.4: the optimizers are functional, so buckets may be applied one
+ * by one in any order; section 4.1: every gradient reaches the shadow exactly
+ * once per iteration).  The W gradient views are folded and (when clipping is
+ * off) the bucket's parameters are updated in the same kernel; when clipping is
+ * on the fold stores the reduced gradient and its sum of squares, and the call
+ * that delivers the last missing bucket of the iteration also enqueues the norm
+ * and the update of every bucket.
  *   d_grad_views  HOST array of W DEVICE pointers; view w holds worker w's
  *                 gradient for this bucket: numel(bucket) elements of
  *                 grad_dtype, contiguous, in the bucket's element order,
- *                 16-byte aligned.  The data must be ready when the call is
- *                 made (or be ordered before it on shadow_bucket_stream) and
- *                 stay unchanged until the work has run (shadow_sync; with
- *                 batch_bytes == 0 also stream order on that stream).  The
- *                 pointer array itself is copied during the call.
+ *                 16-byte aligned.  The pointer array itself is copied during
+ *                 the call.
  *   step          must equal last completed step + 1; buckets of one
  *                 iteration may come in any order, each exactly once.
+ *   ready_event   hipEvent_t recorded by the producer of the views (a copy
+ *                 engine, a collective, a kernel) on ITS stream after the last
+ *                 write to them, or NULL when the views are complete at the
+ *                 time of the call.  The library makes the bucket's stream wait
+ *                 for the event before anything reads the views, also when the
+ *                 launch itself is deferred (batch_bytes > 0); the host never
+ *                 blocks.  The event may be re-recorded after the call returns.
+ * The views must stay unchanged until the work that reads them has run: see
+ * shadow_record_consumed (stream-ordered) or shadow_sync (host-blocking).
  * Asynchronous: returns after buffering or enqueueing.  Errors: EINVAL, EBUCKET, EDUP,
- * ESTEP, EHIP. */
+ * ESTEP, ENOMEM (the replica is untouched), EHIP. */
 int32_t shadow_apply_bucket(shadow_ctx* ctx, uint32_t bucket_id, const void* const* d_grad_views,
-                            uint64_t step);
+                            uint64_t step, void* ready_event);
+
+/* Release side of the views (the counterpart of ready_event): launches what is buffered for the
+ * stream bucket_id runs on and records `event` (the caller's hipEvent_t, not NULL) on that
+ * stream.  Once the event has completed, the views of bucket_id and of every bucket accepted
+ * before it on the same stream (bucket ids congruent modulo num_streams) have been read for the
+ * last time and may be overwritten; the host does not block.  When clipping runs without a
+ * scratch arena the views are read a second time at the end of the iteration: the call then
+ * returns EBUSY while an iteration is open.  Errors: EINVAL, EBUCKET, EBUSY, EHIP. */
+int32_t shadow_record_consumed(shadow_ctx* ctx, uint32_t bucket_id, void* event);
 
 /* Ingest from host memory: the analogue of the shadow node's receive path, which copies
  * reassembled buckets from network buffers into the framework's tensors (section 5).
@@ -237,24 +296,70 @@ int32_t shadow_apply_bucket(shadow_ctx* ctx, uint32_t bucket_id, const void* con
  * slot on a copy stream of the library's own, orders the bucket's fold behind the copy on the
  * bucket's stream and launches it at once (batch_bytes does not apply), so that the copy of
  * one bucket overlaps the fold of the previous ones; a slot is overwritten only after its fold
- * has run.  The host views must stay unchanged until shadow_sync returns.  Same step / bucket
- * rules and errors as shadow_apply_bucket; not available when clipping runs without a scratch
- * arena (EINVAL).  Both ways of delivering buckets may be mixed within an iteration. */
+ * has run.  ready_event (hipEvent_t or NULL) is waited for by the copy stream before the first
+ * copy, for host views that a device-side producer fills.  The host views must stay unchanged
+ * until shadow_sync returns.  Same step / bucket rules and errors as shadow_apply_bucket; not
+ * available when clipping runs without a scratch arena (EINVAL).  Both ways of delivering
+ * buckets may be mixed within an iteration. */
 int32_t shadow_ingest_attach(shadow_ctx* ctx, void* d_ring, uint64_t ring_bytes);
-int32_t shadow_ingest_bucket(shadow_ctx* ctx, uint32_t bucket_id, const void* const* h_grad_views, uint64_t step);
+int32_t shadow_ingest_bucket(shadow_ctx* ctx, uint32_t bucket_id, const void* const* h_grad_views, uint64_t step,
+                             void* ready_event);
 
-/* Copy the replica at the last completed iteration: dst_* are device pointers
- * or pinned host pointers of arena_numel floats each (NULL = skip that array;
- * dst_v is ignored for SGD, which has no second state array).
- * The copies are enqueued after the iteration's last kernel and before any
- * later iteration's work; they have finished when shadow_sync returns.
- * *out_step (host pointer, may be NULL) receives the iteration count.
- * SHADOW_EBUSY if an iteration is partly applied: a checkpoint is only
- * consistent at iteration granularity (section 4, "remain up to date"). */
-int32_t shadow_snapshot(shadow_ctx* ctx, float* dst_param, float* dst_m, float* dst_v, uint64_t* out_step);
+/* ------------------------------------------------------------------------ *
+ * Snapshots: a consistent copy of (param, m, v, step) at an iteration
+ * boundary.  The replica itself is the checkpoint, kept up to date at
+ * per-iteration granularity (section 4 overview); a snapshot is how it is
+ * read without stopping the updates: to serve a recovering trainer or to
+ * consolidate shards (section 4.2.4), or to restore a replica (section 6.5).
+ * Three ways, none of which blocks the host:
+ *
+ * shadow_snapshot: copies enqueued on a copy stream of the library's own,
+ *   behind the last kernel of the last completed iteration.  dst_* are device
+ *   pointers or pinned host pointers of arena_numel floats each (NULL = skip
+ *   that array; dst_v is ignored for SGD, which has no second state array).
+ *   Kernels of later iterations that only read the gradient views (the fold
+ *   with clipping on) run concurrently with the copies; the first kernel that
+ *   writes param, m or v waits for them.  To pinned host memory the copies run
+ *   at PCIe speed, so a large replica stalls for as long as they take: use
+ *   the staged form below for that.  *out_step (host pointer, may be NULL)
+ *   receives the iteration count.  done_event (hipEvent_t or NULL) is recorded
+ *   behind the last copy.  SHADOW_EBUSY if an iteration is partly applied: a
+ *   checkpoint is only consistent at iteration granularity.
+ *
+ * shadow_snapshot_attach + shadow_snapshot_arm: the staged form.  attach lends
+ *   a second set of arenas in device memory (arena_numel floats each, 256-byte
+ *   aligned, d_stage_v NULL for SGD; borrowed until shadow_destroy; at most
+ *   once per context).  arm asks for the state at the END of the iteration that
+ *   is about to start (EBUSY once its first bucket has been accepted): that
+ *   iteration's update kernels then write every new value twice, to the replica
+ *   and to the staging set (12 more bytes per parameter written, nothing read
+ *   again, no separate copy pass and no wait for later iterations).  If
+ *   h_dst_* (pinned host pointers, arena_numel floats each, all three NULL for
+ *   none) are given, the staging set is drained to them on the copy stream
+ *   from the boundary on, concurrently with every later iteration.  The
+ *   staging set must not be read by the caller, and arm returns EBUSY, while a
+ *   drain from it is still running.
+ *
+ * shadow_snapshot_record: records `event` (caller's hipEvent_t) behind the last
+ *   requested snapshot (EBUSY while an armed snapshot's iteration is not yet
+ *   complete; EINVAL if none was ever requested).  shadow_snapshot_wait blocks
+ *   the host until that snapshot is complete and returns its step.
+ * ------------------------------------------------------------------------ */
+int32_t shadow_snapshot(shadow_ctx* ctx, float* dst_param, float* dst_m, float* dst_v, uint64_t* out_step,
+                        void* done_event);
+int32_t shadow_snapshot_attach(shadow_ctx* ctx, float* d_stage_param, float* d_stage_m, float* d_stage_v);
+int32_t shadow_snapshot_arm(shadow_ctx* ctx, float* h_dst_param, float* h_dst_m, float* h_dst_v);
+int32_t shadow_snapshot_record(shadow_ctx* ctx, void* event);
+int32_t shadow_snapshot_wait(shadow_ctx* ctx, uint64_t* out_step);
 
-/* Block the host until everything enqueued by this context has run. */
+/* Block the host until everything enqueued by this context has run, buffered
+ * buckets and snapshot copies included (the shadow must have finished an
+ * iteration before the trainers' next one reaches it, section 6.4). */
 int32_t shadow_sync(shadow_ctx* ctx);
+/* Launch what is buffered, wait for it, release the library's tables, streams
+ * and events.  The arenas hold the state of the last completed iteration (plus
+ * the buckets of an open one) and stay the caller's: the replica can be
+ * recreated over them with start_step (recovery, section 4.2.4). */
 int32_t shadow_destroy(shadow_ctx* ctx);
 
 /* Queries (host pointers out). */
@@ -268,26 +373,10 @@ int32_t shadow_clip_state(shadow_ctx* ctx, float* out_coef, double* out_sumsq);
  * other schedule is evaluated by the caller; section 6).  EBUSY mid-iteration. */
 int32_t shadow_set_lr(shadow_ctx* ctx, float lr);
 
-/* Per-kernel timing with HIP events on the streams the kernels run on.
- * kind: 0 fused fold+AdamW, 1 fold+sum-of-squares, 2 norm finalize, 3 AdamW sweep. */
-enum { SHADOW_K_FOLD_ADAMW = 0, SHADOW_K_FOLD_SUMSQ = 1, SHADOW_K_NORM = 2, SHADOW_K_ADAMW = 3, SHADOW_K_COUNT = 4 };
-int32_t shadow_profile_enable(shadow_ctx* ctx, int32_t on);
-/* Synchronizes, returns and resets the launches and summed duration of one kind. */
-int32_t shadow_profile_read(shadow_ctx* ctx, uint32_t kind, uint64_t* launches, double* total_ms);
-
-/* Plain device-to-device copy kernel of `bytes` (multiple of 16) on `stream`
- * (NULL = default): a known-traffic yardstick for bandwidth counters. */
-int32_t shadow_copy_probe(void* d_dst, const void* d_src, uint64_t bytes, void* stream);
-
 const char* shadow_strerror(int32_t status);
 const char* shadow_last_hip_error(void);
-/* Tuning knobs of the launch shapes (for measurement sweeps): "fold_block" and
- * "adamw_block" (threads per block of the per-bucket kernels / the whole-arena
- * sweep; one of 64, 128, 256, 512, 1024), "fold_lds" and "adamw_lds" (bytes of
- * LDS reserved per block, a multiple of 512 up to 65536, used only to cap how
- * many waves a CU holds: fewer requests in flight keep DRAM rows open longer).
- * Applies to contexts created later. */
-int32_t shadow_set_tunable(const char* name, int64_t value);
+/* Identifies the sources the library was built from (a hash the build passes in). */
+const char* shadow_build_id(void);
 
 #ifdef __cplusplus
 }

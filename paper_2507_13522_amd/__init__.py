@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     K_FOLD_ADAMW,
     K_FOLD_SUMSQ,
     K_NORM,
+    K_SNAPSHOT,
+    LaunchShape,
     OPT_ADAM,
     OPT_ADAMW,
     OPT_SGD,
@@ -24,6 +26,5 @@ from .binding import (  # noqa: F401
     TensorDesc,
     lib,
     shadow_copy_probe,
-    shadow_set_tunable,
     shadow_strerror,
 )

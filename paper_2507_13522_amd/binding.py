@@ -1,4 +1,4 @@
-"""ctypes binding of include/shadow.h: argument marshalling only.
+"""ctypes binding of include/shadow.h and include/shadow_measure.h: argument marshalling only.
 
 Function names follow the C ABI (``shadow_layout_create`` -> ``Layout``,
 ``shadow_init`` -> ``Shadow`` and its methods ``apply_bucket``, ``snapshot``,
@@ -16,7 +16,7 @@ from . import build as _build
 GRAD_F32, GRAD_BF16 = 0, 1
 REDUCE_MEAN, REDUCE_SUM = 0, 1
 OPT_ADAMW, OPT_ADAM, OPT_SGD = 0, 1, 2
-K_FOLD_ADAMW, K_FOLD_SUMSQ, K_NORM, K_ADAMW = 0, 1, 2, 3
+K_FOLD_ADAMW, K_FOLD_SUMSQ, K_NORM, K_ADAMW, K_SNAPSHOT = 0, 1, 2, 3, 4
 
 OK, EINVAL, EBUCKET, EDUP, ESTEP, EBUSY, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
 
@@ -25,16 +25,23 @@ class TensorDesc(C.Structure):
     _fields_ = [("numel", C.c_uint64), ("weight_decay", C.c_uint32), ("reserved", C.c_uint32)]
 
 
+class LaunchShape(C.Structure):
+    """shadow_launch_shape: every field 0 = the library's default."""
+    _fields_ = [("fold_block", C.c_uint32), ("sweep_block", C.c_uint32), ("fold_waves_per_cu", C.c_uint32),
+                ("sweep_waves_per_cu", C.c_uint32), ("max_launch_threads", C.c_uint64)]
+
+
 class HParams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float), ("max_grad_norm", C.c_float), ("num_workers", C.c_uint32),
                 ("grad_dtype", C.c_uint32), ("reduce_op", C.c_uint32), ("num_streams", C.c_uint32),
-                ("optimizer", C.c_uint32), ("batch_bytes", C.c_uint64)]
+                ("optimizer", C.c_uint32), ("batch_bytes", C.c_uint64), ("launch", LaunchShape)]
 
 
 class DevicePlan(C.Structure):
     _fields_ = [("block_bytes", C.c_uint64), ("param_offset", C.c_uint64), ("m_offset", C.c_uint64), ("v_offset", C.c_uint64),
-                ("scratch_offset", C.c_uint64), ("staging_offset", C.c_uint64)]
+                ("scratch_offset", C.c_uint64), ("staging_offset", C.c_uint64), ("snap_param_offset", C.c_uint64),
+                ("snap_m_offset", C.c_uint64), ("snap_v_offset", C.c_uint64)]
 
 
 class ShadowError(RuntimeError):
@@ -56,15 +63,22 @@ _SIGS = {
     "shadow_layout_arena_numel": [C.c_void_p, C.POINTER(C.c_uint64)],
     "shadow_layout_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)],
     "shadow_layout_tensor": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)],
-    "shadow_layout_device_plan": [C.c_void_p, C.c_int32, C.c_uint64, C.POINTER(DevicePlan)],
+    "shadow_layout_device_plan": [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, C.POINTER(DevicePlan)],
     "shadow_layout_arena_stride": [C.c_void_p, C.POINTER(C.c_uint64)],
     "shadow_layout_staging_bytes": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64)],
     "shadow_layout_staging_view": [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64)],
     "shadow_init": [C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(HParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p)],
-    "shadow_apply_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64],
+    "shadow_num_buckets": [C.c_void_p, C.POINTER(C.c_uint32)],
+    "shadow_bucket_info": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)],
+    "shadow_apply_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64, C.c_void_p],
+    "shadow_record_consumed": [C.c_void_p, C.c_uint32, C.c_void_p],
     "shadow_ingest_attach": [C.c_void_p, C.c_void_p, C.c_uint64],
-    "shadow_ingest_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64],
-    "shadow_snapshot": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64)],
+    "shadow_ingest_bucket": [C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64, C.c_void_p],
+    "shadow_snapshot": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64), C.c_void_p],
+    "shadow_snapshot_attach": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "shadow_snapshot_arm": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "shadow_snapshot_record": [C.c_void_p, C.c_void_p],
+    "shadow_snapshot_wait": [C.c_void_p, C.POINTER(C.c_uint64)],
     "shadow_sync": [C.c_void_p],
     "shadow_destroy": [C.c_void_p],
     "shadow_step": [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)],
@@ -73,18 +87,19 @@ _SIGS = {
     "shadow_set_lr": [C.c_void_p, C.c_float],
     "shadow_profile_enable": [C.c_void_p, C.c_int32],
     "shadow_profile_read": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_double)],
-    "shadow_copy_probe": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p],
-    "shadow_set_tunable": [C.c_char_p, C.c_int64],
+    "shadow_copy_probe": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64],
 }
-EXPORTS = sorted(list(_SIGS) + ["shadow_strerror", "shadow_last_hip_error"])
+EXPORTS = sorted(list(_SIGS) + ["shadow_strerror", "shadow_last_hip_error", "shadow_build_id"])
 
 
 def lib() -> C.CDLL:
-    """Load libshadow.so (building it with hipcc only if no built library exists)."""
+    """Load libshadow.so.  The library is built with hipcc first when none exists or when the one that exists
+    was built from other sources than the ones beside it (it embeds a hash of them)."""
     global _lib
     if _lib is None:
         path = _build.LIB
-        if not os.path.exists(path):
+        if _build.stale():
+            print("paper_2507_13522_amd: libshadow.so is missing or older than its sources, building it", flush=True)
             _build.build_library()
         L = C.CDLL(path)
         for name, args in _SIGS.items():
@@ -95,6 +110,10 @@ def lib() -> C.CDLL:
         L.shadow_strerror.restype = C.c_char_p
         L.shadow_last_hip_error.argtypes = []
         L.shadow_last_hip_error.restype = C.c_char_p
+        L.shadow_build_id.argtypes = []
+        L.shadow_build_id.restype = C.c_char_p
+        if L.shadow_build_id().decode() != _build.ID_TAG + _build.source_id():
+            raise RuntimeError(f"{path} was not built from the sources beside it")
         _lib = L
     return _lib
 
@@ -108,12 +127,8 @@ def _check(status: int, where: str) -> None:
         raise ShadowError(status, where)
 
 
-def shadow_set_tunable(name: str, value: int) -> None:
-    _check(lib().shadow_set_tunable(name.encode(), int(value)), "shadow_set_tunable")
-
-
-def shadow_copy_probe(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
-    _check(lib().shadow_copy_probe(dst, src, nbytes, stream), "shadow_copy_probe")
+def shadow_copy_probe(dst: int, src: int, nbytes: int, stream: int = 0, max_launch_threads: int = 0) -> None:
+    _check(lib().shadow_copy_probe(dst, src, nbytes, stream, max_launch_threads), "shadow_copy_probe")
 
 
 class Layout:
@@ -154,11 +169,11 @@ class Layout:
         _check(lib().shadow_layout_tensor(self._h, t, C.byref(b), C.byref(ob), C.byref(oa)), "shadow_layout_tensor")
         return b.value, ob.value, oa.value
 
-    def device_plan(self, with_scratch: bool, staging_bytes: int) -> Optional[DevicePlan]:
-        """Offsets of the arenas and of a gradient buffer of staging_bytes (0: none) inside one 256 GiB allocation,
-        or None when they do not fit."""
+    def device_plan(self, with_scratch: bool, staging_bytes: int, with_snapshot_set: bool = False) -> Optional[DevicePlan]:
+        """Offsets of the arenas, of a snapshot staging set and of a gradient buffer of staging_bytes (0: none) inside
+        one 256 GiB allocation, or None when they do not fit."""
         plan = DevicePlan()
-        rc = lib().shadow_layout_device_plan(self._h, int(with_scratch), staging_bytes, C.byref(plan))
+        rc = lib().shadow_layout_device_plan(self._h, int(with_scratch), int(with_snapshot_set), staging_bytes, C.byref(plan))
         if rc == ENOMEM:
             return None
         _check(rc, "shadow_layout_device_plan")
@@ -214,27 +229,61 @@ class Shadow:
         """Marshal W device addresses once; the result can be passed to apply_bucket repeatedly."""
         return (C.c_void_p * len(ptrs))(*[int(p) for p in ptrs])
 
-    def apply_bucket(self, bucket_id: int, views, step: int) -> None:
-        if not isinstance(views, C.Array):
-            views = self.views_array(views)
-        _check(lib().shadow_apply_bucket(self._h, bucket_id, views, step), "shadow_apply_bucket")
+    def num_buckets(self) -> int:
+        v = C.c_uint32()
+        _check(lib().shadow_num_buckets(self._h, C.byref(v)), "shadow_num_buckets")
+        return v.value
 
-    def try_apply_bucket(self, bucket_id: int, views, step: int) -> int:
+    def bucket_info(self, bucket_id: int) -> Tuple[int, int]:
+        """-> (arena offset, numel)"""
+        off, n = C.c_uint64(), C.c_uint64()
+        _check(lib().shadow_bucket_info(self._h, bucket_id, C.byref(off), C.byref(n)), "shadow_bucket_info")
+        return off.value, n.value
+
+    def apply_bucket(self, bucket_id: int, views, step: int, ready_event: Optional[int] = None) -> None:
+        """ready_event: hipEvent_t handle (int) recorded by the producer of the views, or None."""
         if not isinstance(views, C.Array):
             views = self.views_array(views)
-        return int(lib().shadow_apply_bucket(self._h, bucket_id, views, step))
+        _check(lib().shadow_apply_bucket(self._h, bucket_id, views, step, ready_event or None), "shadow_apply_bucket")
+
+    def try_apply_bucket(self, bucket_id: int, views, step: int, ready_event: Optional[int] = None) -> int:
+        if not isinstance(views, C.Array):
+            views = self.views_array(views)
+        return int(lib().shadow_apply_bucket(self._h, bucket_id, views, step, ready_event or None))
+
+    def record_consumed(self, bucket_id: int, event: int) -> None:
+        _check(lib().shadow_record_consumed(self._h, bucket_id, event), "shadow_record_consumed")
 
     def ingest_attach(self, d_ring: int, ring_bytes: int) -> None:
         _check(lib().shadow_ingest_attach(self._h, d_ring, ring_bytes), "shadow_ingest_attach")
 
-    def ingest_bucket(self, bucket_id: int, host_views, step: int) -> None:
+    def ingest_bucket(self, bucket_id: int, host_views, step: int, ready_event: Optional[int] = None) -> None:
         if not isinstance(host_views, C.Array):
             host_views = self.views_array(host_views)
-        _check(lib().shadow_ingest_bucket(self._h, bucket_id, host_views, step), "shadow_ingest_bucket")
+        _check(lib().shadow_ingest_bucket(self._h, bucket_id, host_views, step, ready_event or None), "shadow_ingest_bucket")
 
-    def snapshot(self, dst_param: Optional[int], dst_m: Optional[int], dst_v: Optional[int]) -> int:
+    def snapshot(self, dst_param: Optional[int], dst_m: Optional[int], dst_v: Optional[int],
+                 done_event: Optional[int] = None) -> int:
         st = C.c_uint64()
-        _check(lib().shadow_snapshot(self._h, dst_param or None, dst_m or None, dst_v or None, C.byref(st)), "shadow_snapshot")
+        _check(lib().shadow_snapshot(self._h, dst_param or None, dst_m or None, dst_v or None, C.byref(st), done_event or None),
+               "shadow_snapshot")
+        return st.value
+
+    def snapshot_attach(self, d_stage_param: int, d_stage_m: int, d_stage_v: Optional[int]) -> None:
+        _check(lib().shadow_snapshot_attach(self._h, d_stage_param, d_stage_m, d_stage_v or None), "shadow_snapshot_attach")
+
+    def snapshot_arm(self, h_dst_param: Optional[int] = None, h_dst_m: Optional[int] = None, h_dst_v: Optional[int] = None) -> None:
+        _check(lib().shadow_snapshot_arm(self._h, h_dst_param or None, h_dst_m or None, h_dst_v or None), "shadow_snapshot_arm")
+
+    def try_snapshot_arm(self, h_dst_param: Optional[int] = None, h_dst_m: Optional[int] = None, h_dst_v: Optional[int] = None) -> int:
+        return int(lib().shadow_snapshot_arm(self._h, h_dst_param or None, h_dst_m or None, h_dst_v or None))
+
+    def snapshot_record(self, event: int) -> None:
+        _check(lib().shadow_snapshot_record(self._h, event), "shadow_snapshot_record")
+
+    def snapshot_wait(self) -> int:
+        st = C.c_uint64()
+        _check(lib().shadow_snapshot_wait(self._h, C.byref(st)), "shadow_snapshot_wait")
         return st.value
 
     def sync(self) -> None:

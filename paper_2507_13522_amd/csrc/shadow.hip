@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/shadow.h"
+#include "../../include/shadow_measure.h"
 
 using namespace shadow;
 
@@ -19,14 +20,30 @@ namespace {
 
 thread_local std::string g_hip_error;
 
-struct Tunables {
-    int64_t fold_block = 1024;    // threads per block of the per-bucket kernels
-    int64_t adamw_block = 256;    // threads per block of the whole-arena AdamW sweep
-    int64_t fold_lds = 0;         // bytes of LDS reserved per block only to cap the waves resident per CU
-    int64_t adamw_lds = 40960;    // 4 blocks of 256 threads (16 waves) per CU
-} g_tune;
-
 constexpr uint64_t kMaxThreadsPerLaunch = 1ull << 31;
+constexpr uint32_t kDefaultFoldBlock = 1024;     // threads per block of the per-bucket kernels
+constexpr uint32_t kDefaultSweepBlock = 256;     // threads per block of the whole-arena optimizer sweep
+constexpr uint32_t kDefaultFoldWaves = 32;       // waves a CU may hold: no bound for the per-bucket kernels,
+constexpr uint32_t kDefaultSweepWaves = 16;      // 4 blocks of 256 threads for the sweep
+constexpr uint32_t kLdsPerCu = 160 * 1024;
+constexpr size_t kMaxSpansPerKind = 65536;
+
+#ifndef SHADOW_BUILD_ID
+#define SHADOW_BUILD_ID "unknown"
+#endif
+
+bool valid_block(uint32_t b) { return b == 64 || b == 128 || b == 256 || b == 512 || b == 1024; }
+
+// Bytes of LDS a block reserves (and never touches) so that a CU holds at most `waves` waves of it.
+uint32_t lds_for_wave_cap(uint32_t block, uint32_t waves)
+{
+    if (waves >= 32) return 0;
+    const uint32_t waves_per_block = block / 64;
+    uint32_t blocks_per_cu = waves / waves_per_block;
+    if (blocks_per_cu < 1) blocks_per_cu = 1;
+    uint32_t lds = (kLdsPerCu / blocks_per_cu) & ~511u;
+    return lds > 65536 ? 65536 : lds;             // the most a launch may ask for without a function attribute
+}
 
 #define HIP_TRY(expr)                                                                         \
     do {                                                                                      \
@@ -81,7 +98,8 @@ struct shadow_ctx {
     double* d_partial = nullptr;
     double* d_stage1 = nullptr;
     uint32_t nstage1 = 0;
-    uint32_t fold_block = 1024, adamw_block = 256, fold_lds = 0, adamw_lds = 40960;
+    uint32_t fold_block = kDefaultFoldBlock, adamw_block = kDefaultSweepBlock, fold_lds = 0, adamw_lds = 0;
+    uint64_t max_launch_threads = kMaxThreadsPerLaunch;
     float* d_coef = nullptr;
     double* d_sumsq = nullptr;
     std::vector<uint32_t> slot_base, slot_count;
@@ -93,8 +111,21 @@ struct shadow_ctx {
     StepScalars sc{};
     uint64_t sc_step = 0;
     std::vector<hipEvent_t> join_ev;      // one per stream
-    hipEvent_t boundary_ev = nullptr;     // after the last kernel / copy at an iteration boundary
+    hipEvent_t boundary_ev = nullptr;     // after the last kernel of an iteration that ends on stream 0
     bool boundary_pending = false;        // streams must wait on boundary_ev before new work
+    // snapshots: copies run on a stream of their own, behind the iteration they belong to
+    hipStream_t snap_stream = nullptr;
+    hipEvent_t state_ev = nullptr;        // replica complete at a boundary (recorded on stream 0 after a join)
+    hipEvent_t snap_ev = nullptr;         // last copy out of the replica has run
+    std::vector<uint8_t> snap_wait;       // per stream: wait for snap_ev before the next kernel that writes the replica
+    float *stage_p = nullptr, *stage_m = nullptr, *stage_v = nullptr;   // lent staging set
+    bool armed = false, snap_active = false;   // armed: the next iteration also writes the staging set; active: this one does
+    float* armed_host[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t drain_ev = nullptr;        // staging set has been drained (or simply completed) for the last armed snapshot
+    bool drain_recorded = false;
+    bool have_snapshot = false;           // some snapshot was requested; last_snap_ev tells which event ends it
+    hipEvent_t last_snap_ev = nullptr;
+    uint64_t last_snap_step = 0;
     std::vector<uint8_t> stream_dirty;    // stream has work since the last join
     bool poisoned = false;
     // buckets accepted but not yet launched, per stream (see hp.batch_bytes)
@@ -124,9 +155,12 @@ bool plan(shadow_layout& L, const uint32_t* fixed, uint64_t cap)
     uint32_t nb = 0;
     if (fixed) {
         uint32_t mx = 0;
-        for (uint32_t t = 0; t < T; ++t) { L.bucket_of[t] = fixed[t]; if (fixed[t] > mx) mx = fixed[t]; }
+        for (uint32_t t = 0; t < T; ++t) {
+            if (fixed[t] >= T) return false;      // dense ids 0..B-1 with B <= T
+            L.bucket_of[t] = fixed[t];
+            if (fixed[t] > mx) mx = fixed[t];
+        }
         nb = T ? mx + 1 : 0;
-        if (nb > T) return false;
         std::vector<uint8_t> used(nb, 0);
         for (uint32_t t = 0; t < T; ++t) used[fixed[t]] = 1;
         for (uint32_t b = 0; b < nb; ++b) if (!used[b]) return false;
@@ -227,17 +261,17 @@ int32_t get_event(shadow_ctx* c, hipEvent_t* out)
 }
 
 struct ProfScope {
-    shadow_ctx* c; uint32_t kind; hipStream_t st; hipEvent_t a = nullptr, b = nullptr; int32_t rc = SHADOW_OK;
+    shadow_ctx* c; uint32_t kind; hipStream_t st; hipEvent_t a = nullptr, b = nullptr; int32_t rc = SHADOW_OK; bool on = true;
     ProfScope(shadow_ctx* c_, uint32_t k, hipStream_t s) : c(c_), kind(k), st(s)
     {
-        if (!c->profile) return;
+        if (!c->profile || c->spans[k].size() >= kMaxSpansPerKind) { on = false; return; }
         rc = get_event(c, &a);
         if (rc == SHADOW_OK) rc = get_event(c, &b);
         if (rc == SHADOW_OK && hipEventRecord(a, st) != hipSuccess) rc = SHADOW_EHIP;
     }
     int32_t end()
     {
-        if (!c->profile || rc != SHADOW_OK) return rc;
+        if (!on || rc != SHADOW_OK) return rc;
         if (hipEventRecord(b, st) != hipSuccess) return SHADOW_EHIP;
         c->spans[kind].push_back({a, b});
         return SHADOW_OK;
@@ -247,18 +281,24 @@ struct ProfScope {
 // update == false: the fold of an arriving bucket (with clipping: sum of squares, reduced gradient stored unless
 // re-fold mode).  update == true: fold + AdamW (clipping off: the only pass; re-fold mode: the second pass, scaled
 // by the clip coefficient).
+SnapSet snap_set(const shadow_ctx* c)
+{
+    return c->snap_active ? SnapSet{c->stage_p, c->stage_m, c->stage_v} : SnapSet{nullptr, nullptr, nullptr};
+}
+
 template <bool BF16, int W>
 void launch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map, bool update)
 {
     const float* coef = c->clip ? c->d_coef : nullptr;
+    const SnapSet sn = snap_set(c);
     if (!update)
         k_fold_sumsq<BF16, W><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->r, c->d_partial, c->sc);
     else if (c->hp.optimizer == SHADOW_OPT_ADAMW)
-        k_fold_adamw<BF16, W, kAdamW><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc);
+        k_fold_adamw<BF16, W, kAdamW><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc, sn);
     else if (c->hp.optimizer == SHADOW_OPT_ADAM)
-        k_fold_adamw<BF16, W, kAdam><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc);
+        k_fold_adamw<BF16, W, kAdam><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc, sn);
     else
-        k_fold_adamw<BF16, W, kSgd><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc);
+        k_fold_adamw<BF16, W, kSgd><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc, sn);
 }
 
 template <bool BF16>
@@ -296,13 +336,28 @@ int32_t mark_boundary(shadow_ctx* c)
     return SHADOW_OK;
 }
 
+// A kernel that writes the replica is about to be enqueued on stream sid: copies of an earlier
+// snapshot that still read the replica must have run first.
+int32_t wait_for_snapshot_copies(shadow_ctx* c, uint32_t sid)
+{
+    if (!c->snap_wait[sid]) return SHADOW_OK;
+    HIP_TRY(hipStreamWaitEvent(c->streams[sid], c->snap_ev, 0));
+    c->snap_wait[sid] = 0;
+    return SHADOW_OK;
+}
+
 // Fold the given buckets on stream st in as few launches as the descriptor allows.
 // ptrs(i) yields the W view pointers of the i-th bucket of the list.
 template <typename PtrFn>
-int32_t launch_buckets(shadow_ctx* c, const uint32_t* ids, size_t count, PtrFn ptrs, hipStream_t st, bool update)
+int32_t launch_buckets(shadow_ctx* c, const uint32_t* ids, size_t count, PtrFn ptrs, uint32_t sid, bool update)
 {
     const uint32_t W = c->hp.num_workers;
     const WdMap map = wd_map(c);
+    hipStream_t st = c->streams[sid];
+    if (update && count) {
+        const int32_t rc = wait_for_snapshot_copies(c, sid);
+        if (rc != SHADOW_OK) return rc;
+    }
     size_t i = 0;
     while (i < count) {
         FoldBatch fb{};
@@ -312,7 +367,7 @@ int32_t launch_buckets(shadow_ctx* c, const uint32_t* ids, size_t count, PtrFn p
         while (i < count && k < kMaxBatch && (k + 1) * W <= kMaxBatchPtrs) {
             const BucketL& b = c->lay.buckets[ids[i]];
             const uint64_t nb = bucket_blocks(c, b.numel, update);
-            if (k > 0 && (blocks + nb) * c->fold_block > kMaxThreadsPerLaunch) break;
+            if (k > 0 && (blocks + nb) * c->fold_block > c->max_launch_threads) break;
             fb.first_block[k] = uint32_t(blocks);
             fb.numel[k] = b.numel;
             fb.arena_off[k] = b.arena_off;
@@ -347,7 +402,7 @@ int32_t flush_stream(shadow_ctx* c, uint32_t sid)
     if (q.empty()) return SHADOW_OK;
     std::vector<uint32_t> ids(q.size());
     for (size_t i = 0; i < q.size(); ++i) ids[i] = q[i].bucket;
-    const int32_t rc = launch_buckets(c, ids.data(), ids.size(), [&](size_t i) { return q[i].ptr; }, c->streams[sid],
+    const int32_t rc = launch_buckets(c, ids.data(), ids.size(), [&](size_t i) { return q[i].ptr; }, sid,
                                       /*update=*/!c->clip);
     if (rc != SHADOW_OK) return rc;
     q.clear();
@@ -372,6 +427,10 @@ void free_ctx(shadow_ctx* c)
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->join_ev) if (e) (void)hipEventDestroy(e);
     if (c->boundary_ev) (void)hipEventDestroy(c->boundary_ev);
+    if (c->state_ev) (void)hipEventDestroy(c->state_ev);
+    if (c->snap_ev) (void)hipEventDestroy(c->snap_ev);
+    if (c->drain_ev) (void)hipEventDestroy(c->drain_ev);
+    if (c->snap_stream) (void)hipStreamDestroy(c->snap_stream);
     for (hipEvent_t e : c->copied_ev) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->consumed_ev) if (e) (void)hipEventDestroy(e);
     if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
@@ -389,7 +448,7 @@ void free_ctx(shadow_ctx* c)
 int32_t build_tables(shadow_ctx* c)
 {
     const shadow_layout& L = c->lay;
-    // runs of equal weight-decay flag over the arena, alignment gaps count as "no decay"
+    // runs of equal weight-decay flag over the arena; an alignment gap is a run of its own kind
     std::vector<uint64_t> start;
     std::vector<uint8_t> flag;
     auto push = [&](uint64_t s, uint8_t f) {
@@ -401,7 +460,7 @@ int32_t build_tables(shadow_ctx* c)
         for (const Seg& sg : b.segs) push(b.arena_off + sg.offset, sg.wd);
         const uint64_t end = b.arena_off + b.numel;
         const uint64_t padded = (end + kAlignElems - 1) / kAlignElems * kAlignElems;
-        if (padded != end) push(end, 0);
+        if (padded != end) push(end, kRunGap);
     }
     if (start.empty()) { start.push_back(0); flag.push_back(0); }
     c->num_runs = uint32_t(start.size());
@@ -541,7 +600,8 @@ int32_t shadow_layout_tensor(const shadow_layout* L, uint32_t tensor, uint32_t* 
     return SHADOW_OK;
 }
 
-int32_t shadow_layout_device_plan(const shadow_layout* L, int32_t with_scratch, uint64_t staging_bytes, shadow_device_plan* plan)
+int32_t shadow_layout_device_plan(const shadow_layout* L, int32_t with_scratch, int32_t with_snapshot_set, uint64_t staging_bytes,
+                                  shadow_device_plan* plan)
 {
     if (!L || !plan) return SHADOW_EINVAL;
     constexpr uint64_t kGiB = 1ull << 30, kRegion = 96 * kGiB, kBlock = 256 * kGiB;
@@ -561,6 +621,12 @@ int32_t shadow_layout_device_plan(const shadow_layout* L, int32_t with_scratch, 
             out.scratch_offset = tail;
             tail += a;
         }
+    }
+    if (with_snapshot_set) {
+        out.snap_param_offset = tail;
+        out.snap_m_offset = tail + a;
+        out.snap_v_offset = tail + 2 * a;
+        tail += 3 * a;
     }
     if (staging_bytes) {
         if (staging_bytes > kBlock) return SHADOW_ENOMEM;
@@ -636,6 +702,9 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
     if ((hp->grad_dtype == SHADOW_GRAD_BF16 ? 2u : 4u) != layout->grad_elem_bytes) return SHADOW_EINVAL;
     if (hp->reduce_op != SHADOW_REDUCE_MEAN && hp->reduce_op != SHADOW_REDUCE_SUM) return SHADOW_EINVAL;
     if (hp->num_streams < 1 || hp->num_streams > SHADOW_MAX_STREAMS) return SHADOW_EINVAL;
+    const shadow_launch_shape& ls = hp->launch;
+    if ((ls.fold_block && !valid_block(ls.fold_block)) || (ls.sweep_block && !valid_block(ls.sweep_block))) return SHADOW_EINVAL;
+    if (ls.fold_waves_per_cu > 32 || ls.sweep_waves_per_cu > 32 || ls.max_launch_threads > kMaxThreadsPerLaunch) return SHADOW_EINVAL;
     const bool clip = hp->max_grad_norm > 0.f;
     if (!clip && d_reduced) return SHADOW_EINVAL;
     if (!aligned(d_param, 256) || !aligned(d_m, 256) || !aligned(d_v, 256) || !aligned(d_reduced, 256)) return SHADOW_EINVAL;
@@ -655,10 +724,12 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
         c->refold = clip && !d_reduced;
         if (c->refold) c->step_views.assign(layout->buckets.size() * size_t(hp->num_workers), nullptr);
         c->completed = start_step;
-        c->fold_block = uint32_t(g_tune.fold_block);
-        c->adamw_block = uint32_t(g_tune.adamw_block);
-        c->fold_lds = uint32_t(g_tune.fold_lds);
-        c->adamw_lds = uint32_t(g_tune.adamw_lds);
+        c->fold_block = ls.fold_block ? ls.fold_block : kDefaultFoldBlock;
+        c->adamw_block = ls.sweep_block ? ls.sweep_block : kDefaultSweepBlock;
+        c->fold_lds = lds_for_wave_cap(c->fold_block, ls.fold_waves_per_cu ? ls.fold_waves_per_cu : kDefaultFoldWaves);
+        c->adamw_lds = lds_for_wave_cap(c->adamw_block, ls.sweep_waves_per_cu ? ls.sweep_waves_per_cu : kDefaultSweepWaves);
+        c->max_launch_threads = ls.max_launch_threads ? ls.max_launch_threads : kMaxThreadsPerLaunch;
+        c->snap_wait.assign(hp->num_streams, 0);
         c->arrived.assign(layout->buckets.size(), 0);
         c->stream_dirty.assign(hp->num_streams, 0);
         c->streams.assign(hp->num_streams, nullptr);
@@ -687,8 +758,15 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
             return fail(SHADOW_EHIP);
         }
     }
-    if (hipEventCreateWithFlags(&c->boundary_ev, hipEventDisableTiming) != hipSuccess) {
+    if (hipEventCreateWithFlags(&c->boundary_ev, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->state_ev, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->snap_ev, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->drain_ev, hipEventDisableTiming) != hipSuccess) {
         g_hip_error = "hipEventCreate failed";
+        return fail(SHADOW_EHIP);
+    }
+    if (hipStreamCreateWithFlags(&c->snap_stream, hipStreamNonBlocking) != hipSuccess) {
+        g_hip_error = "hipStreamCreateWithFlags failed";
         return fail(SHADOW_EHIP);
     }
     rc = build_tables(c);
@@ -712,7 +790,32 @@ int32_t precheck_bucket(const shadow_ctx* c, uint32_t bucket_id, const void* con
     return SHADOW_OK;
 }
 
-int32_t apply_bucket_impl(shadow_ctx* c, uint32_t bucket_id, const void* const* d_grad_views, uint64_t step, bool launch_now)
+// The iteration that just completed was armed: its update kernels wrote the staging set as well.
+// Order the copy stream behind them and drain the staging set to the host arrays, if any were given.
+int32_t finish_armed_snapshot(shadow_ctx* c, uint64_t step)
+{
+    int32_t rc = join_to_stream0(c);
+    if (rc != SHADOW_OK) return rc;
+    HIP_TRY(hipEventRecord(c->state_ev, c->streams[0]));
+    HIP_TRY(hipStreamWaitEvent(c->snap_stream, c->state_ev, 0));
+    const size_t bytes = c->lay.arena_numel * sizeof(float);
+    ProfScope ps(c, SHADOW_K_SNAPSHOT, c->snap_stream);
+    if (ps.rc != SHADOW_OK) return ps.rc;
+    if (c->armed_host[0]) HIP_TRY(hipMemcpyAsync(c->armed_host[0], c->stage_p, bytes, hipMemcpyDeviceToHost, c->snap_stream));
+    if (c->armed_host[1]) HIP_TRY(hipMemcpyAsync(c->armed_host[1], c->stage_m, bytes, hipMemcpyDeviceToHost, c->snap_stream));
+    if (c->armed_host[2] && c->stage_v) HIP_TRY(hipMemcpyAsync(c->armed_host[2], c->stage_v, bytes, hipMemcpyDeviceToHost, c->snap_stream));
+    if (ps.end() != SHADOW_OK) return SHADOW_EHIP;
+    HIP_TRY(hipEventRecord(c->drain_ev, c->snap_stream));
+    c->drain_recorded = true;
+    c->snap_active = false;
+    c->have_snapshot = true;
+    c->last_snap_ev = c->drain_ev;
+    c->last_snap_step = step;
+    return SHADOW_OK;
+}
+
+int32_t apply_bucket_impl(shadow_ctx* c, uint32_t bucket_id, const void* const* d_grad_views, uint64_t step, void* ready_event,
+                          bool launch_now)
 {
     int32_t pre = precheck_bucket(c, bucket_id, d_grad_views, step);
     if (pre != SHADOW_OK) return pre;
@@ -723,31 +826,39 @@ int32_t apply_bucket_impl(shadow_ctx* c, uint32_t bucket_id, const void* const* 
         if (!d_grad_views[w] || !aligned(d_grad_views[w], 16)) return SHADOW_EINVAL;
         pend.ptr[w] = d_grad_views[w];
     }
-    // ---- nothing above changed any state; from here on work is buffered or enqueued ----
     const BucketL& b = c->lay.buckets[bucket_id];
     const uint32_t S = uint32_t(c->streams.size());
     const uint32_t sid = bucket_id % S;
+    try {
+        c->pending[sid].reserve(c->pending[sid].size() + 1);
+    } catch (const std::bad_alloc&) {
+        return SHADOW_ENOMEM;
+    }
+    // The producer of the views: the bucket's stream waits for it here, so every later launch on that
+    // stream (this bucket's fold may be deferred) is ordered behind it.  A wait enqueued for a call
+    // that then fails is harmless.
+    if (ready_event) HIP_TRY(hipStreamWaitEvent(c->streams[sid], static_cast<hipEvent_t>(ready_event), 0));
+    // ---- nothing above changed the replica or the bookkeeping; from here on work is buffered or enqueued ----
     auto hip_fail = [&](const char* what, hipError_t e) {
         g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
         c->poisoned = true;
         return int32_t(SHADOW_EHIP);
     };
+    auto poison = [&](int32_t rc) { c->poisoned = true; return rc; };
     hipError_t e;
     if (c->arrived_count == 0) {
         if (c->sc_step != step) { compute_scalars(c->hp, step, c->sc); c->sc_step = step; }
+        c->snap_active = c->armed;            // an armed snapshot belongs to the iteration that starts now
+        c->armed = false;
         if (c->boundary_pending) {
-            // work of the previous iteration boundary (whole-arena update, snapshot copies) ran on
-            // stream 0; every other stream orders behind it before touching the arenas again
+            // the whole-arena update of the previous iteration ran on stream 0 and read the reduced-gradient
+            // arena; every other stream orders behind it before touching the arenas again
             for (uint32_t s = 1; s < S; ++s)
                 if ((e = hipStreamWaitEvent(c->streams[s], c->boundary_ev, 0)) != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
             c->boundary_pending = false;
         }
     }
-    try {
-        c->pending[sid].push_back(pend);
-    } catch (const std::bad_alloc&) {
-        return SHADOW_ENOMEM;
-    }
+    c->pending[sid].push_back(pend);          // capacity was reserved above
     if (c->refold)
         for (uint32_t w = 0; w < W; ++w) c->step_views[size_t(bucket_id) * W + w] = pend.ptr[w];
     c->pending_bytes[sid] += b.numel * c->lay.grad_elem_bytes * W;
@@ -757,7 +868,7 @@ int32_t apply_bucket_impl(shadow_ctx* c, uint32_t bucket_id, const void* const* 
         if (rc != SHADOW_OK) return rc;
     } else if (launch_now || c->pending_bytes[sid] >= c->hp.batch_bytes) {
         const int32_t rc = flush_stream(c, sid);
-        if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+        if (rc != SHADOW_OK) return poison(rc);
     }
     const WdMap map = wd_map(c);
     c->arrived[bucket_id] = 1;
@@ -765,44 +876,52 @@ int32_t apply_bucket_impl(shadow_ctx* c, uint32_t bucket_id, const void* const* 
     if (c->arrived_count == c->lay.buckets.size()) {
         if (c->clip) {
             int32_t rc = join_to_stream0(c);
-            if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+            if (rc != SHADOW_OK) return poison(rc);
             hipStream_t s0 = c->streams[0];
             {
                 ProfScope ps(c, SHADOW_K_NORM, s0);
-                if (ps.rc != SHADOW_OK) { c->poisoned = true; return ps.rc; }
+                if (ps.rc != SHADOW_OK) return poison(ps.rc);
                 k_norm_stage1<<<c->nstage1, kNormBlock, 0, s0>>>(c->d_partial, c->nslots, c->d_stage1);
                 k_norm_finalize<<<1, kNormBlock, 0, s0>>>(c->d_stage1, c->nstage1, c->hp.max_grad_norm, c->d_coef, c->d_sumsq);
                 if ((e = hipGetLastError()) != hipSuccess) return hip_fail("norm kernel launch", e);
-                if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
+                if (ps.end() != SHADOW_OK) return poison(SHADOW_EHIP);
             }
             if (c->refold) {
                 // the reduced gradient was not stored: fold every bucket again, now scaled by the coefficient
                 std::vector<uint32_t> ids(c->lay.buckets.size());
                 for (size_t i = 0; i < ids.size(); ++i) ids[i] = uint32_t(i);
                 rc = launch_buckets(c, ids.data(), ids.size(),
-                                    [&](size_t i) { return c->step_views.data() + i * W; }, s0, /*update=*/true);
-                if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+                                    [&](size_t i) { return c->step_views.data() + i * W; }, 0, /*update=*/true);
+                if (rc != SHADOW_OK) return poison(rc);
             } else {
+                rc = wait_for_snapshot_copies(c, 0);
+                if (rc != SHADOW_OK) return poison(rc);
                 ProfScope ps(c, SHADOW_K_ADAMW, s0);
-                if (ps.rc != SHADOW_OK) { c->poisoned = true; return ps.rc; }
+                if (ps.rc != SHADOW_OK) return poison(ps.rc);
+                const SnapSet sn = snap_set(c);
                 const uint64_t nvec = c->lay.arena_numel >> 2;      // the arena is a multiple of 64 elements
-                const uint64_t per_launch = kMaxThreadsPerLaunch / c->adamw_block;
+                uint64_t per_launch = c->max_launch_threads / c->adamw_block;
+                if (per_launch < 1) per_launch = 1;
                 const uint64_t blocks = (nvec + c->adamw_block - 1) / c->adamw_block;
                 for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
                     const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
                     if (c->hp.optimizer == SHADOW_OPT_ADAMW)
-                        k_adamw<kAdamW><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc);
+                        k_adamw<kAdamW><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc, sn);
                     else if (c->hp.optimizer == SHADOW_OPT_ADAM)
-                        k_adamw<kAdam><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc);
+                        k_adamw<kAdam><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc, sn);
                     else
-                        k_adamw<kSgd><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc);
+                        k_adamw<kSgd><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc, sn);
                 }
                 if ((e = hipGetLastError()) != hipSuccess) return hip_fail("adamw kernel launch", e);
-                if (ps.end() != SHADOW_OK) { c->poisoned = true; return SHADOW_EHIP; }
+                if (ps.end() != SHADOW_OK) return poison(SHADOW_EHIP);
             }
             c->stream_dirty[0] = 1;
             rc = mark_boundary(c);
-            if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+            if (rc != SHADOW_OK) return poison(rc);
+        }
+        if (c->snap_active) {
+            const int32_t rc = finish_armed_snapshot(c, step);
+            if (rc != SHADOW_OK) return poison(rc);
         }
         std::fill(c->arrived.begin(), c->arrived.end(), uint8_t(0));
         c->arrived_count = 0;
@@ -815,9 +934,41 @@ int32_t apply_bucket_impl(shadow_ctx* c, uint32_t bucket_id, const void* const* 
 
 extern "C" {
 
-int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const* d_grad_views, uint64_t step)
+int32_t shadow_apply_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const* d_grad_views, uint64_t step, void* ready_event)
 {
-    return apply_bucket_impl(c, bucket_id, d_grad_views, step, /*launch_now=*/false);
+    return apply_bucket_impl(c, bucket_id, d_grad_views, step, ready_event, /*launch_now=*/false);
+}
+
+int32_t shadow_num_buckets(const shadow_ctx* c, uint32_t* out)
+{
+    if (!c || !out) return SHADOW_EINVAL;
+    *out = uint32_t(c->lay.buckets.size());
+    return SHADOW_OK;
+}
+
+int32_t shadow_bucket_info(const shadow_ctx* c, uint32_t bucket_id, uint64_t* arena_offset, uint64_t* numel)
+{
+    if (!c) return SHADOW_EINVAL;
+    if (bucket_id >= c->lay.buckets.size()) return SHADOW_EBUCKET;
+    if (arena_offset) *arena_offset = c->lay.buckets[bucket_id].arena_off;
+    if (numel) *numel = c->lay.buckets[bucket_id].numel;
+    return SHADOW_OK;
+}
+
+int32_t shadow_record_consumed(shadow_ctx* c, uint32_t bucket_id, void* event)
+{
+    if (!c || !event) return SHADOW_EINVAL;
+    if (c->poisoned) return SHADOW_EHIP;
+    if (bucket_id >= c->lay.buckets.size()) return SHADOW_EBUCKET;
+    if (c->refold && c->arrived_count != 0) return SHADOW_EBUSY;   // the open iteration's views are read once more at its end
+    const uint32_t sid = bucket_id % uint32_t(c->streams.size());
+    const int32_t rc = flush_stream(c, sid);
+    if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+    // In re-fold mode the last reader of a finished iteration's views ran on stream 0, which
+    // every stream of the next iteration is ordered behind; outside it, on the bucket's stream.
+    hipStream_t st = c->refold ? c->streams[0] : c->streams[sid];
+    HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(event), st));
+    return SHADOW_OK;
 }
 
 int32_t shadow_ingest_attach(shadow_ctx* c, void* d_ring, uint64_t ring_bytes)
@@ -853,7 +1004,7 @@ int32_t shadow_ingest_attach(shadow_ctx* c, void* d_ring, uint64_t ring_bytes)
     return SHADOW_OK;
 }
 
-int32_t shadow_ingest_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const* h_grad_views, uint64_t step)
+int32_t shadow_ingest_bucket(shadow_ctx* c, uint32_t bucket_id, const void* const* h_grad_views, uint64_t step, void* ready_event)
 {
     int32_t pre = precheck_bucket(c, bucket_id, h_grad_views, step);
     if (pre != SHADOW_OK) return pre;
@@ -873,6 +1024,10 @@ int32_t shadow_ingest_bucket(shadow_ctx* c, uint32_t bucket_id, const void* cons
         return int32_t(SHADOW_EHIP);
     };
     hipError_t e;
+    if (ready_event && (e = hipStreamWaitEvent(c->copy_stream, static_cast<hipEvent_t>(ready_event), 0)) != hipSuccess) {
+        g_hip_error = std::string("hipStreamWaitEvent(ready_event): ") + hipGetErrorString(e);
+        return SHADOW_EHIP;                    // nothing was enqueued
+    }
     // the slot's previous occupant must have been folded before it is overwritten
     if (c->consumed_valid[slot] && (e = hipStreamWaitEvent(c->copy_stream, c->consumed_ev[slot], 0)) != hipSuccess)
         return fail("hipStreamWaitEvent", e);
@@ -885,7 +1040,7 @@ int32_t shadow_ingest_bucket(shadow_ctx* c, uint32_t bucket_id, const void* cons
     }
     if ((e = hipEventRecord(c->copied_ev[slot], c->copy_stream)) != hipSuccess) return fail("hipEventRecord", e);
     if ((e = hipStreamWaitEvent(st, c->copied_ev[slot], 0)) != hipSuccess) return fail("hipStreamWaitEvent", e);
-    const int32_t rc = apply_bucket_impl(c, bucket_id, dev_views, step, /*launch_now=*/true);
+    const int32_t rc = apply_bucket_impl(c, bucket_id, dev_views, step, nullptr, /*launch_now=*/true);
     if (rc != SHADOW_OK) { c->poisoned = true; return rc; }      // cannot happen after the precheck except for HIP failures
     if ((e = hipEventRecord(c->consumed_ev[slot], st)) != hipSuccess) return fail("hipEventRecord", e);
     c->consumed_valid[slot] = 1;
@@ -893,21 +1048,106 @@ int32_t shadow_ingest_bucket(shadow_ctx* c, uint32_t bucket_id, const void* cons
     return SHADOW_OK;
 }
 
-int32_t shadow_snapshot(shadow_ctx* c, float* dst_param, float* dst_m, float* dst_v, uint64_t* out_step)
+int32_t shadow_snapshot(shadow_ctx* c, float* dst_param, float* dst_m, float* dst_v, uint64_t* out_step, void* done_event)
 {
     if (!c) return SHADOW_EINVAL;
     if (c->poisoned) return SHADOW_EHIP;
     if (c->arrived_count != 0) return SHADOW_EBUSY;
+    auto poison = [&](int32_t rc) { c->poisoned = true; return rc; };
+    // everything of the completed iteration is ordered before state_ev ...
     int32_t rc = join_to_stream0(c);
-    if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+    if (rc != SHADOW_OK) return poison(rc);
+    HIP_TRY(hipEventRecord(c->state_ev, c->streams[0]));
+    HIP_TRY(hipStreamWaitEvent(c->snap_stream, c->state_ev, 0));
+    // ... the copies run on the copy stream, and only kernels that write the replica wait for them
     const size_t bytes = c->lay.arena_numel * sizeof(float);
-    hipStream_t s0 = c->streams[0];
-    if (dst_param) HIP_TRY(hipMemcpyAsync(dst_param, c->p, bytes, hipMemcpyDefault, s0));
-    if (dst_m) HIP_TRY(hipMemcpyAsync(dst_m, c->m, bytes, hipMemcpyDefault, s0));
-    if (dst_v && c->v) HIP_TRY(hipMemcpyAsync(dst_v, c->v, bytes, hipMemcpyDefault, s0));
-    rc = mark_boundary(c);
-    if (rc != SHADOW_OK) { c->poisoned = true; return rc; }
+    ProfScope ps(c, SHADOW_K_SNAPSHOT, c->snap_stream);
+    if (ps.rc != SHADOW_OK) return ps.rc;
+    hipError_t e = hipSuccess;
+    if (dst_param) e = hipMemcpyAsync(dst_param, c->p, bytes, hipMemcpyDefault, c->snap_stream);
+    if (e == hipSuccess && dst_m) e = hipMemcpyAsync(dst_m, c->m, bytes, hipMemcpyDefault, c->snap_stream);
+    if (e == hipSuccess && dst_v && c->v) e = hipMemcpyAsync(dst_v, c->v, bytes, hipMemcpyDefault, c->snap_stream);
+    // whatever was enqueued, later writers of the replica must stay behind it
+    const hipError_t e2 = hipEventRecord(c->snap_ev, c->snap_stream);
+    std::fill(c->snap_wait.begin(), c->snap_wait.end(), uint8_t(1));
+    if (e != hipSuccess || e2 != hipSuccess) {
+        g_hip_error = std::string("snapshot copy: ") + hipGetErrorString(e != hipSuccess ? e : e2);
+        return poison(SHADOW_EHIP);
+    }
+    if (ps.end() != SHADOW_OK) return poison(SHADOW_EHIP);
+    if (done_event) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(done_event), c->snap_stream));
+    c->have_snapshot = true;
+    c->last_snap_ev = c->snap_ev;
+    c->last_snap_step = c->completed;
     if (out_step) *out_step = c->completed;
+    return SHADOW_OK;
+}
+
+int32_t shadow_snapshot_attach(shadow_ctx* c, float* d_stage_param, float* d_stage_m, float* d_stage_v)
+{
+    if (!c || !d_stage_param || !d_stage_m) return SHADOW_EINVAL;
+    const bool sgd = c->hp.optimizer == SHADOW_OPT_SGD;
+    if (sgd ? d_stage_v != nullptr : d_stage_v == nullptr) return SHADOW_EINVAL;
+    if (!aligned(d_stage_param, 256) || !aligned(d_stage_m, 256) || !aligned(d_stage_v, 256)) return SHADOW_EINVAL;
+    float* all[6] = {d_stage_param, d_stage_m, d_stage_v, c->p, c->m, c->v};
+    for (int i = 0; i < 3; ++i)
+        for (int j = i + 1; j < 6; ++j)
+            if (all[i] && all[i] == all[j]) return SHADOW_EINVAL;
+    if (c->stage_p) return SHADOW_EINVAL;              // at most once
+    if (c->arrived_count != 0) return SHADOW_EBUSY;
+    // the per-bucket kernels never touch the alignment gaps: zero them once so that the staging
+    // set equals the replica everywhere
+    for (const BucketL& b : c->lay.buckets) {
+        const uint64_t end = b.arena_off + b.numel;
+        const uint64_t padded = (end + kAlignElems - 1) / kAlignElems * kAlignElems;
+        if (padded == end) continue;
+        const size_t bytes = (padded - end) * sizeof(float);
+        HIP_TRY(hipMemset(d_stage_param + end, 0, bytes));
+        HIP_TRY(hipMemset(d_stage_m + end, 0, bytes));
+        if (d_stage_v) HIP_TRY(hipMemset(d_stage_v + end, 0, bytes));
+    }
+    HIP_TRY(hipDeviceSynchronize());
+    c->stage_p = d_stage_param;
+    c->stage_m = d_stage_m;
+    c->stage_v = d_stage_v;
+    return SHADOW_OK;
+}
+
+int32_t shadow_snapshot_arm(shadow_ctx* c, float* h_dst_param, float* h_dst_m, float* h_dst_v)
+{
+    if (!c || !c->stage_p) return SHADOW_EINVAL;
+    if (c->poisoned) return SHADOW_EHIP;
+    if (c->arrived_count != 0 || c->armed) return SHADOW_EBUSY;
+    if (c->drain_recorded) {
+        const hipError_t q = hipEventQuery(c->drain_ev);
+        if (q == hipErrorNotReady) return SHADOW_EBUSY;     // the staging set is still being drained
+        if (q != hipSuccess) { g_hip_error = std::string("hipEventQuery: ") + hipGetErrorString(q); return SHADOW_EHIP; }
+    }
+    c->armed = true;
+    c->armed_host[0] = h_dst_param;
+    c->armed_host[1] = h_dst_m;
+    c->armed_host[2] = h_dst_v;
+    return SHADOW_OK;
+}
+
+int32_t shadow_snapshot_record(shadow_ctx* c, void* event)
+{
+    if (!c || !event) return SHADOW_EINVAL;
+    if (c->poisoned) return SHADOW_EHIP;
+    if (c->armed || c->snap_active) return SHADOW_EBUSY;    // the armed iteration has not completed yet
+    if (!c->have_snapshot) return SHADOW_EINVAL;
+    // both kinds of snapshot end on the copy stream, in request order
+    HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(event), c->snap_stream));
+    return SHADOW_OK;
+}
+
+int32_t shadow_snapshot_wait(shadow_ctx* c, uint64_t* out_step)
+{
+    if (!c) return SHADOW_EINVAL;
+    if (c->armed || c->snap_active) return SHADOW_EBUSY;
+    if (!c->have_snapshot) return SHADOW_EINVAL;
+    HIP_TRY(hipEventSynchronize(c->last_snap_ev));
+    if (out_step) *out_step = c->last_snap_step;
     return SHADOW_OK;
 }
 
@@ -919,6 +1159,8 @@ int32_t shadow_sync(shadow_ctx* c)
         if (rc != SHADOW_OK) return rc;
     }
     for (hipStream_t s : c->streams) HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipStreamSynchronize(c->snap_stream));
+    if (c->copy_stream) HIP_TRY(hipStreamSynchronize(c->copy_stream));
     return SHADOW_OK;
 }
 
@@ -927,6 +1169,8 @@ int32_t shadow_destroy(shadow_ctx* c)
     if (!c) return SHADOW_OK;
     if (!c->poisoned) (void)flush_all(c);     // buffered buckets were accepted: their work is owed
     for (hipStream_t s : c->streams) (void)hipStreamSynchronize(s);
+    if (c->snap_stream) (void)hipStreamSynchronize(c->snap_stream);
+    if (c->copy_stream) (void)hipStreamSynchronize(c->copy_stream);
     free_ctx(c);
     return SHADOW_OK;
 }
@@ -994,13 +1238,15 @@ int32_t shadow_profile_read(shadow_ctx* c, uint32_t kind, uint64_t* launches, do
     return SHADOW_OK;
 }
 
-int32_t shadow_copy_probe(void* d_dst, const void* d_src, uint64_t bytes, void* stream)
+int32_t shadow_copy_probe(void* d_dst, const void* d_src, uint64_t bytes, void* stream, uint64_t max_launch_threads)
 {
     if (!d_dst || !d_src || (bytes & 15) || !aligned(d_dst, 16) || !aligned(d_src, 16)) return SHADOW_EINVAL;
+    if (max_launch_threads > kMaxThreadsPerLaunch) return SHADOW_EINVAL;
     const uint64_t n16 = bytes >> 4;
     if (n16 == 0) return SHADOW_OK;
     const uint32_t block = 256;
-    const uint64_t per_launch = kMaxThreadsPerLaunch / block;
+    uint64_t per_launch = (max_launch_threads ? max_launch_threads : kMaxThreadsPerLaunch) / block;
+    if (per_launch < 1) per_launch = 1;
     const uint64_t blocks = (n16 + block - 1) / block;
     for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
         const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
@@ -1028,17 +1274,6 @@ const char* shadow_strerror(int32_t status)
 
 const char* shadow_last_hip_error(void) { return g_hip_error.c_str(); }
 
-int32_t shadow_set_tunable(const char* name, int64_t value)
-{
-    if (!name) return SHADOW_EINVAL;
-    const bool is_block = value == 64 || value == 128 || value == 256 || value == 512 || value == 1024;
-    const bool is_lds = value >= 0 && value <= 65536 && value % 512 == 0;
-    if (!std::strcmp(name, "fold_block") && is_block) g_tune.fold_block = value;
-    else if (!std::strcmp(name, "adamw_block") && is_block) g_tune.adamw_block = value;
-    else if (!std::strcmp(name, "fold_lds") && is_lds) g_tune.fold_lds = value;
-    else if (!std::strcmp(name, "adamw_lds") && is_lds) g_tune.adamw_lds = value;
-    else return SHADOW_EINVAL;
-    return SHADOW_OK;
-}
+const char* shadow_build_id(void) { return SHADOW_BUILD_ID; }
 
 }  // extern "C"

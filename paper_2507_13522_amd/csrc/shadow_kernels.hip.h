@@ -85,8 +85,13 @@ struct StepScalars {
 enum : int { kAdamW = 0, kAdam = 1, kSgd = 2 };
 
 // Weight-decay flag of every arena element: a byte per 1024-element tile
-// (0 = no decay, 1 = decay, 2 = the tile straddles tensors with different
-// flags) plus the sorted run table for the rare straddling tiles.
+// (0 = no decay, 1 = decay, 2 = the tile holds the start of a run, look the
+// element up) plus the sorted run table for those rare tiles.  A run is a
+// stretch of elements with one flag: 0 = no decay, 1 = decay, 2 = alignment gap
+// between two buckets (no parameter lives there; a sweep over the whole arena
+// leaves it untouched, so it stays zero even when the clip coefficient is NaN).
+constexpr uint8_t kTileMixed = 2;
+constexpr uint8_t kRunGap = 2;
 struct WdMap {
     const uint8_t* tile_mode;
     const uint64_t* run_start;   // run k covers [run_start[k], run_start[k+1])
@@ -124,15 +129,17 @@ __device__ __forceinline__ void opt_elem(float& p, float& m, float& v, float g, 
     }
 }
 
-__device__ __forceinline__ bool decay_flag_of(const WdMap& map, uint64_t e)
+__device__ __forceinline__ uint8_t run_flag_of(const WdMap& map, uint64_t e)
 {
     uint32_t lo = 0, hi = map.num_runs;     // largest k with run_start[k] <= e
     while (hi - lo > 1) {
         uint32_t mid = (lo + hi) >> 1;
         if (map.run_start[mid] <= e) lo = mid; else hi = mid;
     }
-    return map.run_flag[lo] != 0;
+    return map.run_flag[lo];
 }
+
+__device__ __forceinline__ bool decay_flag_of(const WdMap& map, uint64_t e) { return run_flag_of(map, e) == 1; }
 
 // ---- fold of 4 consecutive elements ---------------------------------------------------
 // W > 0: compile-time worker count, all loads of a batch issued before the adds (which stay
@@ -267,9 +274,10 @@ __device__ __forceinline__ void step_state4(State4& st, uint64_t e0, const f32x4
 {
 #pragma unroll
     for (int k = 0; k < kVec; ++k) {
-        const bool flag = (st.mode != 2) ? (st.mode != 0) : decay_flag_of(map, e0 + k);
+        const uint8_t f = (st.mode != kTileMixed) ? st.mode : run_flag_of(map, e0 + k);
+        if (f == kRunGap) continue;
         float pk = st.p[k], mk = st.m[k], vk = st.v[k];
-        opt_elem<OPT>(pk, mk, vk, g[k], flag, s);
+        opt_elem<OPT>(pk, mk, vk, g[k], f != 0, s);
         st.p[k] = pk; st.m[k] = mk; st.v[k] = vk;
     }
 }
@@ -282,6 +290,16 @@ __device__ __forceinline__ void store_state4(const State4& st, float* p, float* 
     if constexpr (OPT != kSgd) store_once(reinterpret_cast<f32x4*>(v) + vec, st.v);
 }
 
+// A second set of arenas that receives every new value as well while a snapshot is armed
+// (section 4: the checkpoint is kept at per-iteration granularity; this is how a consistent
+// copy of one iteration's state is taken without a separate pass over the replica).
+// p == nullptr: no snapshot armed (uniform over the launch).
+struct SnapSet {
+    float* p;
+    float* m;
+    float* v;
+};
+
 // ---- kernel: fold + AdamW in one pass (clipping off) ---------------------------------
 // p, m, v are the arenas.  Within its bucket, thread i < n/4 owns elements 4i..4i+3 and
 // thread n/4 owns the (n mod 4) tail elements.
@@ -290,7 +308,7 @@ __device__ __forceinline__ void store_state4(const State4& st, float* p, float* 
 template <bool BF16, int W, int OPT>
 __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* __restrict__ p, float* __restrict__ m,
                                                           float* __restrict__ v, const float* __restrict__ coef, WdMap map,
-                                                          StepScalars s)
+                                                          StepScalars s, SnapSet snap)
 {
     const uint32_t k = bucket_of_block(fb, blockIdx.x);
     const void* const* vp = fb.ptr + k * fb.w;
@@ -307,6 +325,7 @@ __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* _
         if (coef) r = r * (*coef);
         step_state4<OPT>(st, e0, r, map, s);
         store_state4<OPT>(st, pb, mb, vb, vec);
+        if (snap.p) store_state4<OPT>(st, snap.p + off, snap.m + off, OPT == kSgd ? nullptr : snap.v + off, vec);
     } else if (vec == nvec) {
         for (uint64_t e = nvec << 2; e < n; ++e) {
             float g = fold1<BF16>(vp, fb.w, e, s);
@@ -316,6 +335,10 @@ __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* _
             opt_elem<OPT>(pp, mm, vv, g, decay_flag_of(map, off + e), s);
             p[off + e] = pp; m[off + e] = mm;
             if constexpr (OPT != kSgd) v[off + e] = vv;
+            if (snap.p) {
+                snap.p[off + e] = pp; snap.m[off + e] = mm;
+                if constexpr (OPT != kSgd) snap.v[off + e] = vv;
+            }
         }
     }
 }
@@ -507,7 +530,7 @@ __global__ __launch_bounds__(kNormBlock) void k_norm_finalize(const double* __re
 template <int OPT>
 __global__ __launch_bounds__(kMaxBlock) void k_adamw(const float* __restrict__ r, float* __restrict__ p, float* __restrict__ m,
                                                      float* __restrict__ v, uint64_t nvec, uint64_t block_base,
-                                                     const float* __restrict__ coef, WdMap map, StepScalars s)
+                                                     const float* __restrict__ coef, WdMap map, StepScalars s, SnapSet snap)
 {
     const uint64_t vec = (block_base + blockIdx.x) * blockDim.x + threadIdx.x;
     if (vec >= nvec) return;
@@ -517,6 +540,7 @@ __global__ __launch_bounds__(kMaxBlock) void k_adamw(const float* __restrict__ r
     g = g * c;
     step_state4<OPT>(st, vec << 2, g, map, s);
     store_state4<OPT>(st, p, m, v, vec);
+    if (snap.p) store_state4<OPT>(st, snap.p, snap.m, snap.v, vec);
 }
 
 // ---- kernel: plain copy (bandwidth yardstick) ------------------------------------------

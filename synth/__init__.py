@@ -14,10 +14,10 @@ from .rng import (  # noqa: F401
     normal_f32,
     student_t3_f32,
     f32_to_bf16_bits,
-    bf16_bits_to_f32,
     grad_values,
     param_values,
     tiled,
     arrival_order,
 )
 from .workloads import Workload, TensorSpec, get_workload, WORKLOADS  # noqa: F401
+from .inputs import Inputs, TILE_PERIOD  # noqa: F401

@@ -115,13 +115,6 @@ def f32_to_bf16_bits(x: torch.Tensor) -> torch.Tensor:
     return hi.to(torch.int16)
 
 
-def bf16_bits_to_f32(h: torch.Tensor) -> torch.Tensor:
-    """Exact widening of bfloat16 bit patterns (int16) to float32."""
-    b = (h.to(torch.int64) & 0xFFFF) << 16
-    b = torch.where(b >= (1 << 31), b - (1 << 32), b)
-    return b.to(torch.int32).view(torch.float32)
-
-
 def _periodic(idx: torch.Tensor, period: Optional[int]) -> torch.Tensor:
     return idx if not period else idx % int(period)
 

@@ -62,19 +62,41 @@ int main(void)
             CHECK_HIP(hipMemcpy(d_g[b][w], h_g[b][w], n[b] * sizeof(float), hipMemcpyHostToDevice));
         }
     }
-    /* deliver bucket 1 first: arrival order is free; a duplicate is refused */
+    /* the replica knows its bucket map */
+    uint32_t nb_ctx = 0;
+    CHECK_SH(shadow_num_buckets(ctx, &nb_ctx));
+    for (uint32_t b = 0; b < nb; ++b) {
+        uint64_t o2 = 0, n2 = 0;
+        CHECK_SH(shadow_bucket_info(ctx, b, &o2, &n2));
+        if (nb_ctx != nb || o2 != off[b] || n2 != n[b]) { printf("bucket map of the context differs from the layout's\n"); bad = 1; }
+    }
+    /* deliver bucket 1 first: arrival order is free; a duplicate is refused.  Bucket 0's views are
+       produced by copies on a stream of the caller's: the event recorded behind them orders the fold. */
     const void* v1[2] = {d_g[1][0], d_g[1][1]};
     const void* v0[2] = {d_g[0][0], d_g[0][1]};
-    CHECK_SH(shadow_apply_bucket(ctx, 1, v1, 1));
-    if (shadow_apply_bucket(ctx, 1, v1, 1) != SHADOW_EDUP) { printf("duplicate bucket was not refused\n"); bad = 1; }
-    if (shadow_snapshot(ctx, h_out, NULL, NULL, NULL) != SHADOW_EBUSY) { printf("snapshot inside an iteration was not refused\n"); bad = 1; }
-    CHECK_SH(shadow_apply_bucket(ctx, 0, v0, 1));
+    hipStream_t producer;
+    hipEvent_t ready, consumed, snapped;
+    CHECK_HIP(hipStreamCreateWithFlags(&producer, hipStreamNonBlocking));
+    CHECK_HIP(hipEventCreateWithFlags(&ready, hipEventDisableTiming));
+    CHECK_HIP(hipEventCreateWithFlags(&consumed, hipEventDisableTiming));
+    CHECK_HIP(hipEventCreateWithFlags(&snapped, hipEventDisableTiming));
+    CHECK_SH(shadow_apply_bucket(ctx, 1, v1, 1, NULL));
+    if (shadow_apply_bucket(ctx, 1, v1, 1, NULL) != SHADOW_EDUP) { printf("duplicate bucket was not refused\n"); bad = 1; }
+    if (shadow_snapshot(ctx, h_out, NULL, NULL, NULL, NULL) != SHADOW_EBUSY) { printf("snapshot inside an iteration was not refused\n"); bad = 1; }
+    CHECK_HIP(hipEventRecord(ready, producer));
+    CHECK_SH(shadow_apply_bucket(ctx, 0, v0, 1, ready));
+    CHECK_SH(shadow_record_consumed(ctx, 0, consumed));
     uint64_t step = 0;
     float* d_snap;
     CHECK_HIP(hipMalloc((void**)&d_snap, arena * sizeof(float)));
-    CHECK_SH(shadow_snapshot(ctx, d_snap, NULL, NULL, &step));
-    CHECK_SH(shadow_sync(ctx));
+    CHECK_SH(shadow_snapshot(ctx, d_snap, NULL, NULL, &step, snapped));
+    CHECK_HIP(hipEventSynchronize(consumed));
+    CHECK_HIP(hipEventSynchronize(snapped));       /* the copy is complete without a shadow_sync */
     CHECK_HIP(hipMemcpy(h_out, d_snap, arena * sizeof(float), hipMemcpyDeviceToHost));
+    uint64_t waited = 0;
+    CHECK_SH(shadow_snapshot_wait(ctx, &waited));
+    if (waited != 1) { printf("snapshot_wait step %llu\n", (unsigned long long)waited); bad = 1; }
+    CHECK_SH(shadow_sync(ctx));
     if (step != 1) { printf("snapshot step %llu\n", (unsigned long long)step); bad = 1; }
 
     /* closed form, per tensor (tensor t -> bucket, offset) */

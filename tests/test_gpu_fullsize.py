@@ -55,7 +55,7 @@ def pick_buckets(lay: oracle.Layout, budget: int):
 
 
 def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resident: bool, num_streams: int = 2,
-                 batch_bytes: int = 0, refold: bool = False):
+                 batch_bytes: int = 0, refold: bool = False, also_sizes=()):
     wl = synth.get_workload(name)
     say(f"case fullsize {name}: P={wl.num_params} W={wl.num_workers} steps={steps}")
     t_start = time.time()
@@ -77,6 +77,8 @@ def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resi
         ring = [torch.empty(nmax, dtype=g.gdt, device=g.dev) for _ in range(W)]
 
     chosen = pick_buckets(lay, bucket_budget)
+    for size in also_sizes:          # the first bucket of each of these sizes as well, whatever the budget
+        chosen = sorted(set(chosen) | {next(i for i, b in enumerate(lay.buckets) if b.numel == size)})
     say(f"  buckets={B}, oracle recomputes buckets {chosen} ({sum(lay.buckets[b].numel for b in chosen)} elems) "
         f"and {n_scatter} scattered elements")
     # scattered sample: logical indices, their arena positions and decay flags
@@ -161,28 +163,30 @@ def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resi
 
 
 def test_gpt2_small_full():
-    run_fullsize("gpt2s", steps=20, bucket_budget=45_000_000, n_scatter=200_000, resident=True)
+    run_fullsize("gpt2s", steps=20, bucket_budget=45_000_000, n_scatter=2_000_000, resident=True)
 
 
 def test_gpt_1p3b_full():
-    run_fullsize("gpt1p3b", steps=10, bucket_budget=30_000_000, n_scatter=200_000, resident=True)
+    run_fullsize("gpt1p3b", steps=10, bucket_budget=30_000_000, n_scatter=5_000_000, resident=True)
 
 
 def test_llama7b_full():
-    """Same launch configuration as bench.py: one stream, the iteration's buckets folded in as few launches as possible."""
-    run_fullsize("llama7b", steps=5, bucket_budget=60_000_000, n_scatter=500_000, resident=True, num_streams=BENCH_STREAMS,
-                 batch_bytes=BENCH_BATCH_BYTES)
+    """Same launch configuration as bench.py: one stream, the iteration's buckets folded in as few launches as possible.
+    The oracle recomputes, besides the small buckets, a whole 131,072,000-element bucket (embedding / head size), a whole
+    45,088,768-element one (feed-forward matrix) and five million scattered elements."""
+    run_fullsize("llama7b", steps=5, bucket_budget=60_000_000, n_scatter=5_000_000, resident=True, num_streams=BENCH_STREAMS,
+                 batch_bytes=BENCH_BATCH_BYTES, also_sizes=(131_072_000, 45_088_768))
 
 
 def test_llama7b_full_one_launch_per_bucket():
-    run_fullsize("llama7b", steps=2, bucket_budget=60_000_000, n_scatter=500_000, resident=True, num_streams=2, batch_bytes=0)
+    run_fullsize("llama7b", steps=2, bucket_budget=60_000_000, n_scatter=5_000_000, resident=True, num_streams=2, batch_bytes=0)
 
 
 def test_llama7b_single_reduced_gradient_full():
     """W = 1 (the shadow is handed the already-reduced gradient, as in the paper), clipping without a scratch arena."""
-    run_fullsize("llama7b_w1", steps=3, bucket_budget=60_000_000, n_scatter=500_000, resident=True, num_streams=BENCH_STREAMS,
-                 batch_bytes=BENCH_BATCH_BYTES, refold=True)
+    run_fullsize("llama7b_w1", steps=3, bucket_budget=60_000_000, n_scatter=5_000_000, resident=True, num_streams=BENCH_STREAMS,
+                 batch_bytes=BENCH_BATCH_BYTES, refold=True, also_sizes=(131_072_000,))
 
 
 def test_ragged7b_full():
-    run_fullsize("ragged7b", steps=3, bucket_budget=30_000_000, n_scatter=500_000, resident=False, num_streams=4)
+    run_fullsize("ragged7b", steps=3, bucket_budget=30_000_000, n_scatter=5_000_000, resident=False, num_streams=4)

@@ -9,8 +9,8 @@ import oracle
 import paper_2507_13522_amd as sh
 from paper_2507_13522_amd import binding
 import synth
-from harness import (GpuShadow, Inputs, assert_layouts_agree, assert_state_matches, diff, lib_layout, oracle_layout,
-                     run_oracle_full, REL_TOL)
+from harness import (GpuShadow, Inputs, assert_layouts_agree, assert_state_matches, diff, lib_layout, oracle_hparams,
+                     oracle_layout, run_oracle_full, REL_TOL)
 
 pytestmark = pytest.mark.gpu
 
@@ -29,13 +29,14 @@ def custom(name, sizes_flags, W, dtype, clip=0.0, cap=1 << 16, steps=3, dist="no
 
 
 def check_against_oracle(wl, steps=None, num_streams=2, mean=True, every_step=True, exact=True, torch_streams=False,
-                         batch_bytes=0, refold=False, optimizer="adamw"):
+                         batch_bytes=0, refold=False, optimizer="adamw", launch=None):
     """Run both sides on the same inputs and compare param, m, v of every bucket."""
     steps = steps or wl.steps
     inp = Inputs(wl)
     assert_layouts_agree(oracle_layout(wl), lib_layout(wl))
     g = GpuShadow(wl, inp, num_streams=num_streams, mean=mean, torch_streams=torch_streams, batch_bytes=batch_bytes,
-                  refold=refold, optimizer=optimizer)
+                  refold=refold, optimizer=optimizer, launch=launch)
+    assert g.ctx.num_buckets() == len(g.buckets) and all(g.ctx.bucket_info(b) == g.buckets[b][:2] for b in range(len(g.buckets)))
     worst = {}
 
     def on_step(t, orc):
@@ -243,6 +244,14 @@ def test_non_finite_gradients_propagate(clip):
     assert n_bad > 0
     if clip == 0.0:
         assert n_bad <= 3 * len(poison) * 1        # only the poisoned elements (p, m, v each)
+    # the alignment gaps between buckets hold no parameter: they stay zero even though the coefficient is not finite
+    n_gap = 0
+    for (off, n, _), nxt in zip(g.buckets, g.buckets[1:] + [(g.layout.arena_numel, 0, 0)]):
+        for x in (g.p, g.m, g.v) + ((g.r,) if g.r is not None else ()):
+            gap = x[off + n:nxt[0]]
+            n_gap += gap.numel()
+            assert gap.numel() == 0 or (float(gap.abs().max()) == 0.0 and bool(torch.isfinite(gap).all()))
+    assert n_gap > 0
     g.close()
 
 
@@ -360,52 +369,225 @@ def test_clip_arrival_order_invariance():
         assert all(torch.equal(a, b) for a, b in zip(o[:3], outs[0][:3]))
 
 
-def test_snapshot_restore_every_second_step():
-    """Section 6.5 protocol: an interrupted run that restores the shadow's state every second
-    iteration is identical to the uninterrupted run."""
-    say("case snapshot/restore")
-    wl = custom("restore", RAGGED, 4, "bf16", clip=0.01, cap=200_000, steps=6)
+@pytest.mark.parametrize("clip,streams,batch_bytes", [(0.01, 2, 0), (0.0, 3, 300_000)])
+def test_snapshot_restore_every_second_step(clip, streams, batch_bytes):
+    """Section 6.5 protocol: a run that is interrupted and restored from the shadow's state every second
+    iteration equals the uninterrupted run -- here: the ORACLE run straight through, and the oracle restarted
+    from the same snapshots (start_step carries the bias-correction count)."""
+    say("case snapshot/restore", clip, streams, batch_bytes)
+    wl = custom("restore", RAGGED, 4, "bf16", clip=clip, cap=200_000, steps=6)
     inp = Inputs(wl)
-    straight = GpuShadow(wl, inp)
-    for t in range(1, 7):
-        straight.run_step(t)
-    g = GpuShadow(wl, inp)
+    lay = oracle_layout(wl)
+    starts = lay.logical_starts()
+    B = len(lay.buckets)
+    grads = lambda t: {b: [inp.grad_np(t, w, starts[b], lay.buckets[b].numel) for w in range(4)] for b in range(B)}
+    straight = run_oracle_full(wl, inp, 6)
+    g = GpuShadow(wl, inp, num_streams=streams, batch_bytes=batch_bytes)
     A = g.layout.arena_numel
     host = [torch.empty(A, dtype=torch.float32).pin_memory() for _ in range(3)]
+    restarted = None
     for t in range(1, 7):
-        g.run_step(t)
+        g.fill_grads(t)
+        g.apply_step(t)
+        if restarted is not None:
+            restarted.step(grads(t))
         if t % 2 == 0:
-            st = g.ctx.snapshot(*(h.data_ptr() for h in host))
-            g.ctx.sync()
-            assert st == t
+            # the snapshot is enqueued right behind the iteration, with no synchronisation in between
+            assert g.ctx.snapshot(*(h.data_ptr() for h in host)) == t
+            assert g.ctx.snapshot_wait() == t
             g.close()
-            g = GpuShadow(wl, inp, init_from=[h.clone() for h in host], start_step=t)
-    for a, b in zip((g.p, g.m, g.v), (straight.p, straight.m, straight.v)):
-        assert torch.equal(a, b)
+            g = GpuShadow(wl, inp, init_from=[h.clone() for h in host], start_step=t, num_streams=streams, batch_bytes=batch_bytes)
+            cut = lambda h: [h.numpy()[off:off + n].copy() for off, n, _ in g.buckets]
+            if restarted is not None:
+                for b in range(B):      # what the GPU handed over is what the restarted oracle holds
+                    assert_state_matches(tuple(cut(h)[b] for h in host), (restarted.p[b], restarted.m[b], restarted.v[b]),
+                                         f"snapshot at {t} bucket {b}")
+            restarted = oracle.OracleShadow(lay, oracle_hparams(wl), cut(host[0]), start_step=t, m=cut(host[1]), v=cut(host[2]))
+    for b in range(B):
+        got = g.bucket_state(b)
+        assert_state_matches(got, (straight.p[b], straight.m[b], straight.v[b]), f"restored run vs straight oracle, bucket {b}")
+        assert_state_matches(got, (restarted.p[b], restarted.m[b], restarted.v[b]), f"restored run vs restarted oracle, bucket {b}")
     # device-side snapshot equals the arenas, and its step is the completed one
     dst = [torch.empty(A, dtype=torch.float32, device="cuda:0") for _ in range(3)]
     assert g.ctx.snapshot(*(d.data_ptr() for d in dst)) == 6
     g.ctx.sync()
     assert all(torch.equal(a, b) for a, b in zip(dst, (g.p, g.m, g.v)))
-    g.close(); straight.close()
+    g.close()
 
 
-def test_snapshot_orders_before_next_iteration():
-    """A snapshot enqueued at a boundary holds that iteration's state even if the next iteration is enqueued right behind it."""
-    say("case snapshot ordering")
-    wl = custom("snap-order", [(3_000_001, True), (2_000_003, False), (1_000_000, True)], 4, "bf16", clip=0.01, cap=1 << 22, steps=2)
-    g = GpuShadow(wl, Inputs(wl), num_streams=3)
+@pytest.mark.parametrize("clip,streams,batch_bytes", [(0.01, 3, 0), (0.0, 3, 1 << 21), (0.0, 4, 0)])
+def test_snapshot_orders_before_next_iteration(clip, streams, batch_bytes):
+    """A snapshot enqueued at a boundary holds that iteration's state even if the next iteration is enqueued right
+    behind it: the copies run on the library's copy stream, the next iteration's folds may overlap them, and the
+    kernels that write the replica wait (with clipping off those are the fused per-bucket kernels on every stream)."""
+    say("case snapshot ordering", clip, streams, batch_bytes)
+    wl = custom("snap-order", [(3_000_001, True), (2_000_003, False), (1_000_000, True), (500_000, True)], 4, "bf16", clip=clip,
+                cap=1 << 22, steps=3)
+    inp = Inputs(wl)
+    g = GpuShadow(wl, inp, num_streams=streams, batch_bytes=batch_bytes)
     A = g.layout.arena_numel
     g.run_step(1)
     want = [x.clone() for x in (g.p, g.m, g.v)]
     dst = [torch.empty(A, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    host = [torch.empty(A, dtype=torch.float32).pin_memory() for _ in range(3)]
     g.fill_grads(2)
-    g.ctx.snapshot(*(d.data_ptr() for d in dst))
+    done = torch.cuda.Event()
+    done.record()                       # creates the handle; the library records it again behind its copies
+    assert g.ctx.snapshot(*(d.data_ptr() for d in dst)) == 1
+    assert g.ctx.snapshot(*(h.data_ptr() for h in host), done_event=done.cuda_event) == 1
     g.apply_step(2)
+    done.synchronize()                  # the copies are complete; iteration 2 may still be running
+    assert all(torch.equal(a.cpu(), b) for a, b in zip(want, host))
     g.ctx.sync()
     assert all(torch.equal(a, b) for a, b in zip(dst, want))
     assert not torch.equal(g.p, want[0])
+    orc = run_oracle_full(wl, inp, 2)
+    for b in range(len(g.buckets)):
+        assert_state_matches(g.bucket_state(b), (orc.p[b], orc.m[b], orc.v[b]), f"after the snapshot, bucket {b}")
     g.close()
+
+
+@pytest.mark.parametrize("clip,refold,streams,batch_bytes,optimizer", [(0.01, False, 2, 0, "adamw"), (0.0, False, 3, 1 << 20, "adamw"),
+                                                                       (0.01, True, 2, 1 << 62, "adamw"), (0.01, False, 1, 0, "sgd"),
+                                                                       (0.0, False, 2, 0, "adam")])
+def test_staged_snapshot_drains_while_later_iterations_run(clip, refold, streams, batch_bytes, optimizer):
+    """Armed before iteration t, the update kernels of t write the staging set as well; iterations t+1 and t+2 are
+    enqueued at once and the host copy drained from the staging set still equals the ORACLE's state after t."""
+    say("case staged snapshot", clip, refold, streams, batch_bytes, optimizer)
+    W = 1 if refold else 4
+    wl = custom("staged", RAGGED + [(1_500_003, True), (900_001, False)], W, "bf16", clip=clip, cap=1 << 21, steps=5, wd=0.1,
+                lr=0.05 if optimizer == "sgd" else 1e-3)
+    inp = Inputs(wl)
+    g = GpuShadow(wl, inp, num_streams=streams, batch_bytes=batch_bytes, refold=refold, optimizer=optimizer, snapshot_set=True)
+    A, B = g.layout.arena_numel, len(g.buckets)
+    sgd = optimizer == "sgd"
+    host = [torch.full((A,), 7.0, dtype=torch.float32).pin_memory() for _ in range(3)]
+    states = {}
+    run_oracle_full(wl, inp, 5, optimizer=optimizer,
+                    on_step=lambda t, o: states.__setitem__(t, [[x.copy() for x in o.p], [x.copy() for x in o.m], [x.copy() for x in o.v]]))
+    with pytest.raises(sh.ShadowError) as e:
+        g.ctx.snapshot_wait()                       # nothing requested yet
+    assert e.value.status == binding.EINVAL
+    # every iteration's views are kept on the device, so that nothing below has to wait for the host
+    views = {}
+    for t in range(1, 6):
+        g.fill_grads(t)
+        views[t] = g._stage.clone()
+
+    def apply(t):
+        cur = torch.cuda.current_stream()
+        if t > 1 and not refold:
+            # release side: the previous iteration's readers of the views, stream by stream
+            for s in range(min(streams, B)):
+                rel = torch.cuda.Event()
+                rel.record()
+                g.ctx.record_consumed(s, rel.cuda_event)
+                cur.wait_event(rel)
+        elif t > 1:
+            rel = torch.cuda.Event()
+            rel.record()
+            g.ctx.record_consumed(0, rel.cuda_event)        # folding twice: the last reader ran at the iteration's end
+            cur.wait_event(rel)
+        g._stage.copy_(views[t])        # on torch's stream ...
+        ev = torch.cuda.Event()
+        ev.record()
+        for b in range(B):              # ... ordered before the folds by the event, never by the host
+            g.ctx.apply_bucket(b, g._views[b], t, ready_event=ev.cuda_event)
+
+    apply(1)
+    g.ctx.snapshot_arm(host[0].data_ptr(), host[1].data_ptr(), None if sgd else host[2].data_ptr())
+    assert g.ctx.try_snapshot_arm() == binding.EBUSY            # already armed
+    with pytest.raises(sh.ShadowError) as e:
+        g.ctx.snapshot_wait()                                   # its iteration has not run yet
+    assert e.value.status == binding.EBUSY
+    apply(2)                                                    # the armed iteration
+    apply(3)
+    apply(4)
+    assert g.ctx.snapshot_wait() == 2
+    ref = states[2]
+    for b, (off, n, _) in enumerate(g.buckets):
+        got = tuple(h.numpy()[off:off + n] for h in host)
+        if sgd:
+            got = got[:2] + (ref[2][b],)
+        assert_state_matches(got, (ref[0][b], ref[1][b], ref[2][b]), f"drained snapshot of iteration 2, bucket {b}")
+    # the staging set has the replica's layout: its alignment gaps are zero as well
+    for (off, n, _), nxt in zip(g.buckets[:-1], g.buckets[1:]):
+        assert nxt[0] == off + n or float(host[0][off + n:nxt[0]].abs().max()) == 0.0
+    # arming is refused inside an iteration
+    g.ctx.sync()
+    g._stage.copy_(views[5])
+    torch.cuda.synchronize()
+    g.ctx.apply_bucket(0, g._views[0], 5)
+    if B > 1:
+        assert g.ctx.try_snapshot_arm() == binding.EBUSY
+    for b in range(1, B):
+        g.ctx.apply_bucket(b, g._views[b], 5)
+    g.ctx.sync()
+    o = states[5]
+    for b in range(B):
+        assert_state_matches(g.bucket_state(b), (o[0][b], o[1][b], o[2][b]), f"replica after 5 iterations, bucket {b}")
+    g.close()
+
+
+def test_views_from_a_foreign_stream_need_no_host_sync():
+    """The views are written by a producer on its own stream (here: a slow kernel, then copies); the event recorded
+    behind them is all the ordering there is, also when the fold launch is deferred (batch_bytes > 0)."""
+    say("case foreign producer stream")
+    for bb, clip in ((0, 0.0), (1 << 62, 0.01), (1 << 20, 0.0)):
+        wl = custom("producer", RAGGED + [(2_000_003, True)], 4, "bf16", clip=clip, cap=1 << 21, steps=2)
+        inp = Inputs(wl)
+        g = GpuShadow(wl, inp, num_streams=2, batch_bytes=bb)
+        B = len(g.buckets)
+        src = {}
+        for t in (1, 2):
+            g.fill_grads(t)
+            src[t] = g._stage.clone()
+        torch.cuda.synchronize()
+        producer = torch.cuda.Stream()
+        for t in (1, 2):
+            with torch.cuda.stream(producer):
+                if t == 2:
+                    # the views of iteration 1 must have been read before they are overwritten
+                    for s in range(min(2, B)):
+                        rel = torch.cuda.Event()
+                        rel.record(producer)
+                        g.ctx.record_consumed(s, rel.cuda_event)
+                        producer.wait_event(rel)
+                g._stage.fill_(0x7F)                  # garbage (NaN patterns) until the producer is done
+                torch.cuda._sleep(2_000_000)         # some milliseconds: a fold that did not wait would read the garbage
+                g._stage.copy_(src[t], non_blocking=True)
+                evs = []
+                for b in range(B):
+                    ev = torch.cuda.Event()
+                    ev.record(producer)
+                    evs.append(ev)
+            for b in range(B):
+                g.ctx.apply_bucket(b, g._views[b], t, ready_event=evs[b].cuda_event)
+        orc = run_oracle_full(wl, inp, 2)
+        for b in range(B):
+            assert_state_matches(g.bucket_state(b), (orc.p[b], orc.m[b], orc.v[b]), f"producer bb={bb} bucket {b}")
+        g.close()
+
+
+@pytest.mark.parametrize("W,dtype,clip,refold", [(8, "bf16", 0.01, False), (3, "f32", 0.0, False), (1, "bf16", 0.01, True)])
+def test_logical_launches_split_into_several(W, dtype, clip, refold):
+    """max_launch_threads far below the sizes involved: the whole-arena sweep, the fold batches and the copy kernel
+    each run as many launches (block_base > 0), with the bits of the oracle."""
+    say("case split launches", W, dtype, clip, refold)
+    wl = custom("split", RAGGED, W, dtype, clip=clip, cap=200_000, steps=3, random_arrival=True)
+    nthreads = sum(n for n, _ in RAGGED) // 4
+    for limit, fold_block, sweep_block in ((4096, 1024, 256), (1000, 256, 64), (1 << 16, 512, 1024)):
+        assert nthreads // limit >= 1
+        launch = sh.LaunchShape(fold_block=fold_block, sweep_block=sweep_block, max_launch_threads=limit,
+                                fold_waves_per_cu=16, sweep_waves_per_cu=8)
+        check_against_oracle(wl, num_streams=2, batch_bytes=1 << 62, refold=refold, launch=launch)
+    n = 3_000_000
+    src = torch.randint(0, 255, (n * 16,), dtype=torch.uint8, device="cuda:0")
+    for limit in (0, 1 << 20, 5000, 256, 1):
+        dst = torch.zeros_like(src)
+        sh.shadow_copy_probe(dst.data_ptr(), src.data_ptr(), n * 16, 0, limit)
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst), limit
 
 
 def test_exactly_once_errors_leave_state_untouched():

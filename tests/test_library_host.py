@@ -16,10 +16,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "shadow.h")).read()
+    import glob
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert [os.path.basename(h) for h in headers] == ["shadow.h", "shadow_measure.h"]
+    hdr = "".join(open(h).read() for h in headers)
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(shadow_[a-z_0-9]+)\s*\(", hdr))
-    assert len(declared) >= 20
+    assert len(declared) >= 30
     L = sh.lib()
     for name in sorted(declared):
         assert hasattr(L, name), f"{name} declared in shadow.h but not exported"
@@ -72,6 +75,10 @@ def test_layout_rejects_bad_arguments():
     with pytest.raises(sh.ShadowError):
         sh.Layout([(5, True), (6, True)], 2, 0, [0, 2])      # ids not dense
     with pytest.raises(sh.ShadowError):
+        sh.Layout([(5, True), (6, True)], 2, 0, [0, 0xFFFFFFFF])   # id + 1 would wrap to zero buckets
+    with pytest.raises(sh.ShadowError):
+        sh.Layout([(5, True), (6, True)], 2, 0, [1, 1])      # bucket 0 unused
+    with pytest.raises(sh.ShadowError):
         sh.Layout([((1 << 48) + 1, True)], 2, 1 << 20)           # beyond the largest supported tensor
     with pytest.raises(sh.ShadowError):
         sh.Layout([(1 << 47, True), (1 << 47, True), (8, True)], 2, 1 << 20)   # total beyond 2^48 elements
@@ -89,7 +96,8 @@ def test_init_validates_before_touching_the_gpu():
                 grad_dtype=sh.GRAD_BF16, reduce_op=sh.REDUCE_MEAN, num_streams=1)
     bad = [dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0), dict(lr=-1.0), dict(num_workers=0), dict(num_workers=65),
            dict(grad_dtype=7), dict(grad_dtype=sh.GRAD_F32), dict(reduce_op=3), dict(num_streams=0), dict(num_streams=17),
-           dict(weight_decay=-1.0)]
+           dict(weight_decay=-1.0), dict(launch=sh.LaunchShape(fold_block=96)), dict(launch=sh.LaunchShape(sweep_block=2048)),
+           dict(launch=sh.LaunchShape(sweep_waves_per_cu=33)), dict(launch=sh.LaunchShape(max_launch_threads=(1 << 31) + 1))]
     for kw in bad:
         hp = sh.HParams(**{**good, **kw})
         with pytest.raises(sh.ShadowError) as e:
@@ -107,11 +115,18 @@ def test_init_validates_before_touching_the_gpu():
 def test_null_handles_are_rejected():
     L = sh.lib()
     assert L.shadow_sync(None) == binding.EINVAL
-    assert L.shadow_apply_bucket(None, 0, None, 1) == binding.EINVAL
-    assert L.shadow_snapshot(None, None, None, None, None) == binding.EINVAL
+    assert L.shadow_apply_bucket(None, 0, None, 1, None) == binding.EINVAL
+    assert L.shadow_ingest_bucket(None, 0, None, 1, None) == binding.EINVAL
+    assert L.shadow_record_consumed(None, 0, None) == binding.EINVAL
+    assert L.shadow_snapshot(None, None, None, None, None, None) == binding.EINVAL
+    assert L.shadow_snapshot_attach(None, None, None, None) == binding.EINVAL
+    assert L.shadow_snapshot_arm(None, None, None, None) == binding.EINVAL
+    assert L.shadow_snapshot_record(None, None) == binding.EINVAL
+    assert L.shadow_snapshot_wait(None, None) == binding.EINVAL
+    assert L.shadow_num_buckets(None, None) == binding.EINVAL
+    assert L.shadow_bucket_info(None, 0, None, None) == binding.EINVAL
     assert L.shadow_destroy(None) == binding.OK
-    assert L.shadow_set_tunable(b"nope", 1) == binding.EINVAL
-    assert L.shadow_copy_probe(None, None, 16, None) == binding.EINVAL
+    assert L.shadow_copy_probe(None, None, 16, None, 0) == binding.EINVAL
 
 
 def test_placement_advice():
@@ -150,6 +165,7 @@ def test_device_plan():
         W = wl.num_workers
         plan = lay.device_plan(scratch, lay.staging_bytes(W))
         assert plan is not None and plan.block_bytes == 256 * G
+        assert (plan.snap_param_offset, plan.snap_m_offset, plan.snap_v_offset) == (0, 0, 0)
         arena = lay.arena_numel * 4
         parts = [(plan.param_offset, arena), (plan.m_offset, arena), (plan.v_offset, arena), (plan.staging_offset, lay.staging_bytes(W))]
         if scratch:
@@ -170,8 +186,16 @@ def test_device_plan():
     assert lay.device_plan(True, lay.staging_bytes(32)) is None                # 32 resident views of 7B: 400 GiB
     ring = lay.device_plan(True, 100 << 30)                                   # a 100 GiB ring instead
     assert ring is not None and ring.staging_offset + (100 << 30) <= ring.block_bytes
+    # a snapshot staging set (a second param, m, v) follows v; the views' buffer comes last
+    snap = lay.device_plan(True, 48 << 30, True)
+    assert snap is not None
+    arena = lay.arena_numel * 4
+    assert snap.snap_param_offset >= snap.v_offset + arena and snap.snap_m_offset >= snap.snap_param_offset + arena
+    assert snap.snap_v_offset >= snap.snap_m_offset + arena and snap.staging_offset >= snap.snap_v_offset + arena
+    assert snap.staging_offset + (48 << 30) <= snap.block_bytes
+    assert lay.device_plan(True, lay.staging_bytes(8), True) is None          # all views resident AND a second state: too much
     huge = sh.Layout([(13_000_000_000, True)], 4, 1 << 40)
     assert huge.device_plan(False, 0) is None                          # two arenas exceed one region
     L = binding.lib()
-    assert L.shadow_layout_device_plan(None, 0, 0, None) == binding.EINVAL
+    assert L.shadow_layout_device_plan(None, 0, 0, 0, None) == binding.EINVAL
 

@@ -50,7 +50,6 @@ def test_bf16_rounding_matches_library():
     x = torch.randn(100_000) * 1e-3
     bits = synth.f32_to_bf16_bits(x)
     assert torch.equal(bits.view(torch.bfloat16), x.to(torch.bfloat16))
-    assert torch.equal(synth.bf16_bits_to_f32(bits), x.to(torch.bfloat16).float())
 
 
 def test_arrival_order_is_a_permutation():
