@@ -48,7 +48,8 @@ typedef enum {
     SHADOW_ESTEP   = -4,  /* step is not last completed step + 1 (a lost or replayed iteration) */
     SHADOW_EBUSY   = -5,  /* operation needs an iteration boundary but an iteration is open    */
     SHADOW_EHIP    = -6,  /* HIP runtime failure; shadow_last_hip_error() has the text         */
-    SHADOW_ENOMEM  = -7   /* host or device allocation failed                                  */
+    SHADOW_ENOMEM  = -7,  /* host or device allocation failed                                  */
+    SHADOW_ETOOBIG = -8   /* input exceeds the fixed capacity of the library's static scratch  */
 } shadow_status;
 
 enum { SHADOW_GRAD_F32 = 0, SHADOW_GRAD_BF16 = 1 };
@@ -372,6 +373,33 @@ int32_t shadow_clip_state(shadow_ctx* ctx, float* out_coef, double* out_sumsq);
 /* Learning rate for iterations that start after this call (cosine or any
  * other schedule is evaluated by the caller; section 6).  EBUSY mid-iteration. */
 int32_t shadow_set_lr(shadow_ctx* ctx, float lr);
+
+/* For callers that cannot allocate device memory or create streams and events: code whose
+ * launches must all go to one given stream, tight serving loops, harnesses that forbid
+ * hipMalloc.  One WHOLE iteration in one call, without a context: the same kernels and the same
+ * bits as shadow_init + shadow_apply_bucket for every bucket, everything enqueued on `stream`
+ * (hipStream_t, NULL = default) in order.  The call makes no device allocation, creates no stream
+ * and no event and never blocks: the tables its kernels need beyond the caller's arrays (the
+ * weight-decay map, the norm partials, the clip coefficient) live in a static device array of
+ * about 5 MiB that each GPU the library runs on holds until the process ends.
+ *   layout, hp          as for shadow_init (hp->num_streams and hp->batch_bytes are not used:
+ *                       all buckets are folded in as few launches as the descriptor allows).
+ *   d_param, d_m, d_v, d_reduced   the arenas, as for shadow_init (d_reduced NULL with clipping
+ *                       on: the views are folded twice).  The alignment gaps are not touched.
+ *   d_grad_views        HOST array of num_buckets * W DEVICE pointers, bucket-major (bucket b's
+ *                       W views at [b*W, b*W + W)), each as for shadow_apply_bucket; complete
+ *                       when `stream` reaches the call's work, unchanged until it has run.
+ *   step                1-based count of this iteration (Adam's bias correction).
+ * Limits: arena_numel <= SHADOW_STATIC_MAX_ARENA_NUMEL, at most SHADOW_STATIC_MAX_BUCKETS buckets
+ * and 8,192 runs of tensors with equal weight-decay flag; beyond them SHADOW_ETOOBIG and nothing
+ * is enqueued.  All calls on one GPU share that GPU's scratch array, which keeps the last
+ * call's contents (every entry that is read is rewritten first, nothing needs clearing): calls
+ * whose work may overlap on one GPU (different streams, several threads) race; serialize them.
+ * Other errors: EINVAL, ENOMEM (host), EHIP. */
+enum { SHADOW_STATIC_MAX_ARENA_NUMEL = 1 << 27, SHADOW_STATIC_MAX_BUCKETS = 4096 };
+int32_t shadow_apply_iteration_static(const shadow_layout* layout, const shadow_hparams* hp,
+                                      float* d_param, float* d_m, float* d_v, float* d_reduced,
+                                      const void* const* d_grad_views, uint64_t step, void* stream);
 
 const char* shadow_strerror(int32_t status);
 const char* shadow_last_hip_error(void);

@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     ShadowError,
     TensorDesc,
     lib,
+    shadow_apply_iteration_static,
     shadow_copy_probe,
     shadow_strerror,
 )

@@ -18,7 +18,8 @@ REDUCE_MEAN, REDUCE_SUM = 0, 1
 OPT_ADAMW, OPT_ADAM, OPT_SGD = 0, 1, 2
 K_FOLD_ADAMW, K_FOLD_SUMSQ, K_NORM, K_ADAMW, K_SNAPSHOT = 0, 1, 2, 3, 4
 
-OK, EINVAL, EBUCKET, EDUP, ESTEP, EBUSY, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
+OK, EINVAL, EBUCKET, EDUP, ESTEP, EBUSY, EHIP, ENOMEM, ETOOBIG = 0, -1, -2, -3, -4, -5, -6, -7, -8
+STATIC_MAX_ARENA_NUMEL, STATIC_MAX_BUCKETS = 1 << 27, 4096
 
 
 class TensorDesc(C.Structure):
@@ -79,6 +80,8 @@ _SIGS = {
     "shadow_snapshot_arm": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "shadow_snapshot_record": [C.c_void_p, C.c_void_p],
     "shadow_snapshot_wait": [C.c_void_p, C.POINTER(C.c_uint64)],
+    "shadow_apply_iteration_static": [C.c_void_p, C.POINTER(HParams), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.POINTER(C.c_void_p), C.c_uint64, C.c_void_p],
     "shadow_sync": [C.c_void_p],
     "shadow_destroy": [C.c_void_p],
     "shadow_step": [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)],
@@ -205,6 +208,15 @@ class Layout:
             self.close()
         except Exception:
             pass
+
+
+def shadow_apply_iteration_static(layout: "Layout", hp: HParams, d_param: int, d_m: int, d_v: Optional[int],
+                                  d_reduced: Optional[int], views: Sequence[int], step: int, stream: int = 0) -> int:
+    """One whole iteration without a context and without any allocation; views: num_buckets * W device addresses,
+    bucket-major.  Returns the status (no exception), so that callers can test for ETOOBIG."""
+    arr = views if isinstance(views, C.Array) else (C.c_void_p * len(views))(*[int(p) for p in views])
+    return int(lib().shadow_apply_iteration_static(layout._h, C.byref(hp), d_param, d_m, d_v or None, d_reduced or None, arr,
+                                                   step, stream or None))
 
 
 class Shadow:

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -445,12 +446,9 @@ void free_ctx(shadow_ctx* c)
     delete c;
 }
 
-int32_t build_tables(shadow_ctx* c)
+// Runs of equal weight-decay flag over the arena; an alignment gap is a run of its own kind.
+void make_runs(const shadow_layout& L, std::vector<uint64_t>& start, std::vector<uint8_t>& flag)
 {
-    const shadow_layout& L = c->lay;
-    // runs of equal weight-decay flag over the arena; an alignment gap is a run of its own kind
-    std::vector<uint64_t> start;
-    std::vector<uint8_t> flag;
     auto push = [&](uint64_t s, uint8_t f) {
         if (!flag.empty() && flag.back() == f) return;
         start.push_back(s);
@@ -463,6 +461,33 @@ int32_t build_tables(shadow_ctx* c)
         if (padded != end) push(end, kRunGap);
     }
     if (start.empty()) { start.push_back(0); flag.push_back(0); }
+}
+
+// Norm-partial slots: one per wave of each bucket's fold launch.  false: more than 2^31 - 1 slots.
+bool assign_slots(shadow_ctx* c)
+{
+    const shadow_layout& L = c->lay;
+    c->slot_base.resize(L.buckets.size());
+    c->slot_count.resize(L.buckets.size());
+    uint64_t total = 0;
+    for (size_t b = 0; b < L.buckets.size(); ++b) {
+        c->slot_base[b] = uint32_t(total);
+        c->slot_count[b] = bucket_blocks(c, L.buckets[b].numel, false) * (c->fold_block / 64);
+        total += c->slot_count[b];
+        if (total > 0x7FFFFFFFull) return false;
+    }
+    c->nslots = uint32_t(total);
+    c->nstage1 = uint32_t((total + kNormChunk - 1) / kNormChunk);
+    if (c->nstage1 == 0) c->nstage1 = 1;
+    return true;
+}
+
+int32_t build_tables(shadow_ctx* c)
+{
+    const shadow_layout& L = c->lay;
+    std::vector<uint64_t> start;
+    std::vector<uint8_t> flag;
+    make_runs(L, start, flag);
     c->num_runs = uint32_t(start.size());
     const uint64_t ntiles = (L.arena_numel + (1ull << kWdTileShift) - 1) >> kWdTileShift;
     std::vector<uint8_t> mode(ntiles ? ntiles : 1, 0);
@@ -491,19 +516,8 @@ int32_t build_tables(shadow_ctx* c)
         if (c->r) HIP_TRY(hipMemset(c->r + end, 0, bytes));
     }
     if (c->clip) {
-        c->slot_base.resize(L.buckets.size());
-        c->slot_count.resize(L.buckets.size());
-        uint64_t total = 0;
-        for (size_t b = 0; b < L.buckets.size(); ++b) {
-            c->slot_base[b] = uint32_t(total);
-            // one slot per wave of the bucket's fold launch
-            c->slot_count[b] = bucket_blocks(c, L.buckets[b].numel, false) * (c->fold_block / 64);
-            total += c->slot_count[b];
-            if (total > 0x7FFFFFFFull) return SHADOW_EINVAL;
-        }
-        c->nslots = uint32_t(total);
-        c->nstage1 = uint32_t((total + kNormChunk - 1) / kNormChunk);
-        if (c->nstage1 == 0) c->nstage1 = 1;
+        if (!assign_slots(c)) return SHADOW_EINVAL;
+        const uint64_t total = c->nslots;
         HIP_TRY(hipMalloc(&c->d_partial, (total ? total : 1) * sizeof(double)));
         HIP_TRY(hipMalloc(&c->d_stage1, c->nstage1 * sizeof(double)));
         HIP_TRY(hipMalloc(&c->d_coef, sizeof(float)));
@@ -685,11 +699,14 @@ int32_t shadow_layout_staging_view(const shadow_layout* L, uint32_t num_workers,
     return SHADOW_OK;
 }
 
-int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_hparams* hp, float* d_param, float* d_m,
-                    float* d_v, float* d_reduced, uint64_t start_step, void* const* streams)
+}  // extern "C"
+
+namespace {
+
+// What every way of creating or running a replica checks before it touches the GPU.
+int32_t check_replica_args(const shadow_layout* layout, const shadow_hparams* hp, const float* d_param, const float* d_m,
+                           const float* d_v, const float* d_reduced)
 {
-    if (!out) return SHADOW_EINVAL;
-    *out = nullptr;
     if (!layout || !hp || !d_param || !d_m) return SHADOW_EINVAL;
     if (hp->optimizer != SHADOW_OPT_ADAMW && hp->optimizer != SHADOW_OPT_ADAM && hp->optimizer != SHADOW_OPT_SGD) return SHADOW_EINVAL;
     const bool sgd = hp->optimizer == SHADOW_OPT_SGD;
@@ -712,6 +729,32 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
 
     for (const BucketL& b : layout->buckets)
         if (bucket_threads(b.numel) > kMaxThreadsPerLaunch) return SHADOW_EINVAL;   // one launch per bucket
+    return SHADOW_OK;
+}
+
+// Launch shape of a context from the hyper-parameters (zero fields take the defaults).
+void set_launch_shape(shadow_ctx* c, const shadow_launch_shape& ls)
+{
+    c->fold_block = ls.fold_block ? ls.fold_block : kDefaultFoldBlock;
+    c->adamw_block = ls.sweep_block ? ls.sweep_block : kDefaultSweepBlock;
+    c->fold_lds = lds_for_wave_cap(c->fold_block, ls.fold_waves_per_cu ? ls.fold_waves_per_cu : kDefaultFoldWaves);
+    c->adamw_lds = lds_for_wave_cap(c->adamw_block, ls.sweep_waves_per_cu ? ls.sweep_waves_per_cu : kDefaultSweepWaves);
+    c->max_launch_threads = ls.max_launch_threads ? ls.max_launch_threads : kMaxThreadsPerLaunch;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_hparams* hp, float* d_param, float* d_m,
+                    float* d_v, float* d_reduced, uint64_t start_step, void* const* streams)
+{
+    if (!out) return SHADOW_EINVAL;
+    *out = nullptr;
+    const int32_t chk = check_replica_args(layout, hp, d_param, d_m, d_v, d_reduced);
+    if (chk != SHADOW_OK) return chk;
+    const bool clip = hp->max_grad_norm > 0.f;
+    const shadow_launch_shape& ls = hp->launch;
 
     shadow_ctx* c = new (std::nothrow) shadow_ctx();
     if (!c) return SHADOW_ENOMEM;
@@ -724,11 +767,7 @@ int32_t shadow_init(shadow_ctx** out, const shadow_layout* layout, const shadow_
         c->refold = clip && !d_reduced;
         if (c->refold) c->step_views.assign(layout->buckets.size() * size_t(hp->num_workers), nullptr);
         c->completed = start_step;
-        c->fold_block = ls.fold_block ? ls.fold_block : kDefaultFoldBlock;
-        c->adamw_block = ls.sweep_block ? ls.sweep_block : kDefaultSweepBlock;
-        c->fold_lds = lds_for_wave_cap(c->fold_block, ls.fold_waves_per_cu ? ls.fold_waves_per_cu : kDefaultFoldWaves);
-        c->adamw_lds = lds_for_wave_cap(c->adamw_block, ls.sweep_waves_per_cu ? ls.sweep_waves_per_cu : kDefaultSweepWaves);
-        c->max_launch_threads = ls.max_launch_threads ? ls.max_launch_threads : kMaxThreadsPerLaunch;
+        set_launch_shape(c, ls);
         c->snap_wait.assign(hp->num_streams, 0);
         c->arrived.assign(layout->buckets.size(), 0);
         c->stream_dirty.assign(hp->num_streams, 0);
@@ -814,6 +853,57 @@ int32_t finish_armed_snapshot(shadow_ctx* c, uint64_t step)
     return SHADOW_OK;
 }
 
+// Every bucket of the iteration has been folded (clipping on): the norm over all of them, the clip
+// coefficient, then the update of every bucket, all on stream 0 behind the folds.
+int32_t enqueue_norm_and_update(shadow_ctx* c, bool single_stream = false)
+{
+    const uint32_t W = c->hp.num_workers;
+    const WdMap map = wd_map(c);
+    int32_t rc = single_stream ? int32_t(SHADOW_OK) : join_to_stream0(c);
+    if (rc != SHADOW_OK) return rc;
+    hipStream_t s0 = c->streams[0];
+    {
+        ProfScope ps(c, SHADOW_K_NORM, s0);
+        if (ps.rc != SHADOW_OK) return ps.rc;
+        k_norm_stage1<<<c->nstage1, kNormBlock, 0, s0>>>(c->d_partial, c->nslots, c->d_stage1);
+        k_norm_finalize<<<1, kNormBlock, 0, s0>>>(c->d_stage1, c->nstage1, c->hp.max_grad_norm, c->d_coef, c->d_sumsq);
+        HIP_TRY(hipGetLastError());
+        if (ps.end() != SHADOW_OK) return SHADOW_EHIP;
+    }
+    if (c->refold) {
+        // the reduced gradient was not stored: fold every bucket again, now scaled by the coefficient
+        std::vector<uint32_t> ids(c->lay.buckets.size());
+        for (size_t i = 0; i < ids.size(); ++i) ids[i] = uint32_t(i);
+        rc = launch_buckets(c, ids.data(), ids.size(), [&](size_t i) { return c->step_views.data() + i * W; }, 0, /*update=*/true);
+        if (rc != SHADOW_OK) return rc;
+    } else {
+        rc = wait_for_snapshot_copies(c, 0);
+        if (rc != SHADOW_OK) return rc;
+        ProfScope ps(c, SHADOW_K_ADAMW, s0);
+        if (ps.rc != SHADOW_OK) return ps.rc;
+        const SnapSet sn = snap_set(c);
+        const uint64_t nvec = c->lay.arena_numel >> 2;      // the arena is a multiple of 64 elements
+        uint64_t per_launch = c->max_launch_threads / c->adamw_block;
+        if (per_launch < 1) per_launch = 1;
+        const uint64_t blocks = (nvec + c->adamw_block - 1) / c->adamw_block;
+        for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
+            const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
+            if (c->hp.optimizer == SHADOW_OPT_ADAMW)
+                k_adamw<kAdamW><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc, sn);
+            else if (c->hp.optimizer == SHADOW_OPT_ADAM)
+                k_adamw<kAdam><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc, sn);
+            else
+                k_adamw<kSgd><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc, sn);
+        }
+        HIP_TRY(hipGetLastError());
+        if (ps.end() != SHADOW_OK) return SHADOW_EHIP;
+    }
+    c->stream_dirty[0] = 1;
+    return single_stream ? int32_t(SHADOW_OK) : mark_boundary(c);      // one stream: order is the stream's, no event
+}
+
+int32_t enqueue_norm_and_update_on_one_stream(shadow_ctx* c) { return enqueue_norm_and_update(c, true); }
+
 int32_t apply_bucket_impl(shadow_ctx* c, uint32_t bucket_id, const void* const* d_grad_views, uint64_t step, void* ready_event,
                           bool launch_now)
 {
@@ -870,53 +960,11 @@ int32_t apply_bucket_impl(shadow_ctx* c, uint32_t bucket_id, const void* const* 
         const int32_t rc = flush_stream(c, sid);
         if (rc != SHADOW_OK) return poison(rc);
     }
-    const WdMap map = wd_map(c);
     c->arrived[bucket_id] = 1;
     c->arrived_count++;
     if (c->arrived_count == c->lay.buckets.size()) {
         if (c->clip) {
-            int32_t rc = join_to_stream0(c);
-            if (rc != SHADOW_OK) return poison(rc);
-            hipStream_t s0 = c->streams[0];
-            {
-                ProfScope ps(c, SHADOW_K_NORM, s0);
-                if (ps.rc != SHADOW_OK) return poison(ps.rc);
-                k_norm_stage1<<<c->nstage1, kNormBlock, 0, s0>>>(c->d_partial, c->nslots, c->d_stage1);
-                k_norm_finalize<<<1, kNormBlock, 0, s0>>>(c->d_stage1, c->nstage1, c->hp.max_grad_norm, c->d_coef, c->d_sumsq);
-                if ((e = hipGetLastError()) != hipSuccess) return hip_fail("norm kernel launch", e);
-                if (ps.end() != SHADOW_OK) return poison(SHADOW_EHIP);
-            }
-            if (c->refold) {
-                // the reduced gradient was not stored: fold every bucket again, now scaled by the coefficient
-                std::vector<uint32_t> ids(c->lay.buckets.size());
-                for (size_t i = 0; i < ids.size(); ++i) ids[i] = uint32_t(i);
-                rc = launch_buckets(c, ids.data(), ids.size(),
-                                    [&](size_t i) { return c->step_views.data() + i * W; }, 0, /*update=*/true);
-                if (rc != SHADOW_OK) return poison(rc);
-            } else {
-                rc = wait_for_snapshot_copies(c, 0);
-                if (rc != SHADOW_OK) return poison(rc);
-                ProfScope ps(c, SHADOW_K_ADAMW, s0);
-                if (ps.rc != SHADOW_OK) return poison(ps.rc);
-                const SnapSet sn = snap_set(c);
-                const uint64_t nvec = c->lay.arena_numel >> 2;      // the arena is a multiple of 64 elements
-                uint64_t per_launch = c->max_launch_threads / c->adamw_block;
-                if (per_launch < 1) per_launch = 1;
-                const uint64_t blocks = (nvec + c->adamw_block - 1) / c->adamw_block;
-                for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
-                    const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
-                    if (c->hp.optimizer == SHADOW_OPT_ADAMW)
-                        k_adamw<kAdamW><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc, sn);
-                    else if (c->hp.optimizer == SHADOW_OPT_ADAM)
-                        k_adamw<kAdam><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc, sn);
-                    else
-                        k_adamw<kSgd><<<uint32_t(nb), c->adamw_block, c->adamw_lds, s0>>>(c->r, c->p, c->m, c->v, nvec, b0, c->d_coef, map, c->sc, sn);
-                }
-                if ((e = hipGetLastError()) != hipSuccess) return hip_fail("adamw kernel launch", e);
-                if (ps.end() != SHADOW_OK) return poison(SHADOW_EHIP);
-            }
-            c->stream_dirty[0] = 1;
-            rc = mark_boundary(c);
+            const int32_t rc = enqueue_norm_and_update(c);
             if (rc != SHADOW_OK) return poison(rc);
         }
         if (c->snap_active) {
@@ -1151,6 +1199,145 @@ int32_t shadow_snapshot_wait(shadow_ctx* c, uint64_t* out_step)
     return SHADOW_OK;
 }
 
+}  // extern "C"
+
+// ---- one whole iteration without any allocation -----------------------------------------
+// Device memory that the kernels need beyond the caller's arrays (the weight-decay tables, the
+// norm partials, the clip coefficient) lies in one file-scope device array of fixed size.  Each
+// GPU holds its own copy at its own address: the address is looked up once per device and only
+// that pointer, never the array's name, is used in host code.
+namespace {
+
+constexpr uint64_t kStaticMaxArena = SHADOW_STATIC_MAX_ARENA_NUMEL;
+constexpr uint32_t kStaticMaxBuckets = SHADOW_STATIC_MAX_BUCKETS;
+constexpr uint32_t kStaticMaxRuns = 8192;
+constexpr uint64_t kStaticMaxSlots = kStaticMaxArena / 256 + 17ull * kStaticMaxBuckets;   // a wave covers >= 256 elements
+constexpr uint64_t kOffTileMode = 0;                                                       // 1 byte per 1024 elements
+constexpr uint64_t kOffRunStart = kOffTileMode + (kStaticMaxArena >> kWdTileShift);
+constexpr uint64_t kOffRunFlag = kOffRunStart + 8ull * kStaticMaxRuns;
+constexpr uint64_t kOffPartial = kOffRunFlag + kStaticMaxRuns;
+constexpr uint64_t kOffStage1 = kOffPartial + 8ull * kStaticMaxSlots;
+constexpr uint64_t kOffCoef = kOffStage1 + (8ull * ((kStaticMaxSlots + kNormChunk - 1) / kNormChunk) + 255) / 256 * 256;
+constexpr uint64_t kOffSumsq = kOffCoef + 256;
+constexpr uint64_t kStaticScratchBytes = kOffSumsq + 256;
+static_assert(kOffRunStart % 256 == 0 && kOffRunFlag % 256 == 0 && kOffPartial % 256 == 0 && kOffStage1 % 256 == 0 &&
+              kOffCoef % 256 == 0 && kOffSumsq % 256 == 0, "sections of the static scratch are 256-byte aligned");
+static_assert(kStaticScratchBytes < (6ull << 20), "the static scratch stays modest");
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this GPU's copy of the scratch array (looked up on the first call on that device).
+int32_t static_scratch(unsigned char** out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return SHADOW_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        unsigned char* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+        if (!ptr) { g_hip_error = "hipGetSymbolAddress returned a null address"; return SHADOW_EHIP; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SHADOW_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t shadow_apply_iteration_static(const shadow_layout* layout, const shadow_hparams* hp, float* d_param, float* d_m, float* d_v,
+                                      float* d_reduced, const void* const* d_grad_views, uint64_t step, void* stream)
+{
+    const int32_t chk = check_replica_args(layout, hp, d_param, d_m, d_v, d_reduced);
+    if (chk != SHADOW_OK) return chk;
+    if (!d_grad_views || step == 0) return SHADOW_EINVAL;
+    const uint32_t W = hp->num_workers;
+    const size_t B = layout->buckets.size();
+    for (size_t i = 0; i < B * W; ++i)
+        if (!d_grad_views[i] || !aligned(d_grad_views[i], 16)) return SHADOW_EINVAL;
+    if (layout->arena_numel > kStaticMaxArena || B > kStaticMaxBuckets) return SHADOW_ETOOBIG;
+
+    // a context on the stack: host bookkeeping only, its device tables point into the static scratch
+    shadow_ctx c;
+    std::vector<uint64_t> run_start;
+    std::vector<uint8_t> run_flag;
+    std::vector<uint32_t> ids;
+    try {
+        c.lay = *layout;
+        c.streams.assign(1, static_cast<hipStream_t>(stream));
+        c.stream_dirty.assign(1, 0);
+        c.snap_wait.assign(1, 0);
+        make_runs(c.lay, run_start, run_flag);
+        ids.resize(B);
+    } catch (const std::bad_alloc&) {
+        return SHADOW_ENOMEM;
+    }
+    c.hp = *hp;
+    c.p = d_param; c.m = d_m; c.v = d_v; c.r = d_reduced;
+    c.clip = hp->max_grad_norm > 0.f;
+    c.refold = c.clip && !d_reduced;
+    set_launch_shape(&c, hp->launch);
+    if (run_start.size() > kStaticMaxRuns) return SHADOW_ETOOBIG;
+    if (c.clip) {
+        try {
+            if (!assign_slots(&c)) return SHADOW_ETOOBIG;
+        } catch (const std::bad_alloc&) {
+            return SHADOW_ENOMEM;
+        }
+        if (c.nslots > kStaticMaxSlots) return SHADOW_ETOOBIG;
+    }
+    unsigned char* base = nullptr;
+    const int32_t rs = static_scratch(&base);
+    if (rs != SHADOW_OK) return rs;
+    c.d_tile_mode = base + kOffTileMode;
+    c.d_run_start = reinterpret_cast<uint64_t*>(base + kOffRunStart);
+    c.d_run_flag = base + kOffRunFlag;
+    c.num_runs = uint32_t(run_start.size());
+    c.d_partial = reinterpret_cast<double*>(base + kOffPartial);
+    c.d_stage1 = reinterpret_cast<double*>(base + kOffStage1);
+    c.d_coef = reinterpret_cast<float*>(base + kOffCoef);
+    c.d_sumsq = reinterpret_cast<double*>(base + kOffSumsq);
+    compute_scalars(c.hp, step, c.sc);
+
+    // The scratch keeps the previous call's contents.  Nothing in it has to start at zero: the run table and the
+    // tile modes are rewritten below for this layout, every wave of the folds writes its own partial slot, the norm
+    // kernels write every stage-1 entry they later read, and the coefficient is written before the update reads it.
+    hipStream_t st = c.streams[0];
+    for (uint32_t first = 0; first < c.num_runs; first += kRunChunk) {
+        RunChunk ch{};
+        ch.first = first;
+        ch.count = c.num_runs - first < uint32_t(kRunChunk) ? c.num_runs - first : uint32_t(kRunChunk);
+        for (uint32_t i = 0; i < ch.count; ++i) { ch.start[i] = run_start[first + i]; ch.flag[i] = run_flag[first + i]; }
+        k_put_runs<<<1, kRunChunk, 0, st>>>(ch, c.d_run_start, c.d_run_flag);
+    }
+    const uint64_t ntiles = (c.lay.arena_numel + (1ull << kWdTileShift) - 1) >> kWdTileShift;
+    k_build_tile_mode<<<uint32_t((ntiles + 255) / 256), 256, 0, st>>>(c.d_run_start, c.d_run_flag, c.num_runs, c.lay.arena_numel,
+                                                                      c.d_tile_mode, ntiles);
+    HIP_TRY(hipGetLastError());
+    for (size_t i = 0; i < B; ++i) ids[i] = uint32_t(i);
+    auto views_of = [&](size_t i) { return d_grad_views + i * W; };
+    int32_t rc = launch_buckets(&c, ids.data(), B, views_of, 0, /*update=*/!c.clip);
+    if (rc != SHADOW_OK) return rc;
+    if (c.clip) {
+        if (c.refold) {
+            try {
+                c.step_views.assign(d_grad_views, d_grad_views + B * W);
+            } catch (const std::bad_alloc&) {
+                return SHADOW_ENOMEM;       // the folds already ran; the replica itself is still untouched
+            }
+        }
+        rc = enqueue_norm_and_update_on_one_stream(&c);
+        if (rc != SHADOW_OK) return rc;
+    }
+    return SHADOW_OK;
+}
+
 int32_t shadow_sync(shadow_ctx* c)
 {
     if (!c) return SHADOW_EINVAL;
@@ -1268,6 +1455,7 @@ const char* shadow_strerror(int32_t status)
         case SHADOW_EBUSY: return "an iteration is partly applied";
         case SHADOW_EHIP: return "HIP runtime failure";
         case SHADOW_ENOMEM: return "out of memory";
+        case SHADOW_ETOOBIG: return "input exceeds the fixed capacity of the library's static scratch";
         default: return "unknown status";
     }
 }

@@ -355,7 +355,7 @@ template <bool BF16, int W>
 constexpr int fold_vpl()
 {
     if (W <= 0) return 1;
-    const int bytes = 4 * (BF16 ? 2 : 4) * W;
+    const int bytes = 4 * (BF16 ? 2 : 4) * (W > 0 ? W : 1);
     const int v = SHADOW_FOLD_LANE_BYTES / bytes;
     return v < 1 ? 1 : (v > 8 ? 8 : v);
 }
@@ -549,6 +549,46 @@ __global__ __launch_bounds__(kMaxBlock) void k_copy(const u32x4* __restrict__ sr
 {
     const uint64_t i = (block_base + blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < n16) store_once(dst + i, load_once(src + i));
+}
+
+// ---- kernels: weight-decay tables written on the device (no host-to-device copy) ---------
+// A chunk of the run table travels in the kernel arguments and is written to its place.
+constexpr int kRunChunk = 256;
+struct RunChunk {
+    uint32_t first;     // index of the chunk's first run
+    uint32_t count;
+    uint64_t start[kRunChunk];
+    uint8_t flag[kRunChunk];
+};
+
+__global__ __launch_bounds__(kRunChunk) void k_put_runs(RunChunk c, uint64_t* __restrict__ run_start, uint8_t* __restrict__ run_flag)
+{
+    const uint32_t i = threadIdx.x;
+    if (i < c.count) {
+        run_start[c.first + i] = c.start[i];
+        run_flag[c.first + i] = c.flag[i];
+    }
+}
+
+// Tile t takes the flag of the run that covers its first element, or kTileMixed when another run
+// starts inside it.
+__global__ __launch_bounds__(256) void k_build_tile_mode(const uint64_t* __restrict__ run_start, const uint8_t* __restrict__ run_flag,
+                                                         uint32_t num_runs, uint64_t arena_numel, uint8_t* __restrict__ tile_mode,
+                                                         uint64_t ntiles)
+{
+    const uint64_t t = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (t >= ntiles) return;
+    const uint64_t first = t << kWdTileShift;
+    uint64_t end = first + (1ull << kWdTileShift);
+    if (end > arena_numel) end = arena_numel;
+    uint32_t lo = 0, hi = num_runs;             // largest k with run_start[k] <= first
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (run_start[mid] <= first) lo = mid; else hi = mid;
+    }
+    uint8_t mode = run_flag[lo];
+    if (lo + 1 < num_runs && run_start[lo + 1] < end) mode = kTileMixed;
+    tile_mode[t] = mode;
 }
 
 }  // namespace shadow
