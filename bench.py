@@ -149,14 +149,17 @@ def main() -> int:
     ap.add_argument("--refold", action="store_true",
                     help="clipping without a scratch arena: fold the views twice instead of storing the reduced gradient")
     ap.add_argument("--optimizer", default="adamw", choices=["adamw", "adam", "sgd"])
+    ap.add_argument("--no-clip", action="store_true", help="run the workload without global-norm clipping (fused kernel)")
     ap.add_argument("--ingest-slots", type=int, default=0,
                     help="hand the buckets over as pinned HOST views through a device ring of this many slots "
                          "(PCIe-inclusive rate; never the headline value)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-yardstick", action="store_true", help="skip timing the plain copy kernel")
     ap.add_argument("--fold-block", type=int, default=0)
+    ap.add_argument("--fused-block", type=int, default=0)
     ap.add_argument("--sweep-block", type=int, default=0)
-    ap.add_argument("--fold-waves", type=int, default=0, help="upper bound on the waves per CU of the per-bucket kernels")
+    ap.add_argument("--fold-waves", type=int, default=0, help="upper bound on the waves per CU of the fold + sum-of-squares kernel")
+    ap.add_argument("--fused-waves", type=int, default=0, help="upper bound on the waves per CU of the fold + optimizer kernel")
     ap.add_argument("--sweep-waves", type=int, default=0, help="upper bound on the waves per CU of the optimizer sweep")
     ap.add_argument("--placement", default="auto", choices=["auto", "plan", "stride", "separate"],
                     help="where the arenas and views lie in HBM (auto: the library's device plan, else its stride advice)")
@@ -188,16 +191,18 @@ def main() -> int:
     batch_bytes = BENCH_BATCH_BYTES if args.batch_mib is None else args.batch_mib << 20
 
     default_settings = (args.streams is None and args.batch_mib is None and args.optimizer == "adamw" and not args.ingest_slots
-                        and not args.fold_block and not args.sweep_block and not args.fold_waves and not args.sweep_waves
-                        and args.placement == "auto" and not args.snapshot_every and not args.view_ring_gib)
+                        and not args.fold_block and not args.fused_block and not args.sweep_block and not args.fold_waves and not args.fused_waves and not args.sweep_waves
+                        and args.placement == "auto" and not args.snapshot_every and not args.view_ring_gib and not args.no_clip)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
-    launch = sh.LaunchShape(fold_block=args.fold_block, sweep_block=args.sweep_block, fold_waves_per_cu=args.fold_waves,
-                            sweep_waves_per_cu=args.sweep_waves)
+    launch = sh.LaunchShape(fold_block=args.fold_block, fused_block=args.fused_block, sweep_block=args.sweep_block, fold_waves_per_cu=args.fold_waves,
+                            fused_waves_per_cu=args.fused_waves, sweep_waves_per_cu=args.sweep_waves)
 
     wl = synth.get_workload(args.workload)
+    if args.no_clip:
+        wl.max_grad_norm = 0.0
     inputs = Inputs(wl, period=TILE_PERIOD)
     ingest = args.ingest_slots > 0
     # all W views of every bucket resident when they fit beside the replica; otherwise (W = 32 at 7B: 445 GB) the
@@ -212,14 +217,15 @@ def main() -> int:
             ring_bytes = VIEW_RING_BYTES if not snapshots else 32 << 30
         lay.close()
     g = GpuShadow(wl, inputs, num_streams=streams, batch_bytes=batch_bytes, refold=args.refold, optimizer=args.optimizer,
-                  resident_grads=not ingest, ring_bytes=ring_bytes, placement=args.placement, snapshot_set=staged, launch=launch)
+                  resident_grads=not ingest, ring_bytes=ring_bytes, placement=args.placement,
+                  snapshot_set=staged or (snapshots and not args.snapshot_host), attach_snapshot_set=staged, launch=launch)
     P = g.layout.num_params
     A = g.layout.arena_numel
     snap_dev = snap_host = None
     if snapshots and args.snapshot_host:
         snap_host = [torch.empty(A, dtype=torch.float32).pin_memory() for _ in range(3)]
     elif snapshots and not staged:
-        snap_dev = [torch.empty(A, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+        snap_dev = g.snap                      # a second set of arenas, placed with everything else
     snap_taken, snap_skipped = 0, 0
 
     def before_step(i):

@@ -70,19 +70,27 @@ typedef struct {
 
 /* Launch shape of the kernels of ONE replica (part of shadow_hparams; every field 0 = the
  * library's default, which is what was measured fastest on MI355X).  Results never depend on it.
- *   fold_block, sweep_block   threads per block of the per-bucket kernels (default 1024) and of
- *                             the whole-arena optimizer sweep (default 256): 64, 128, 256, 512 or 1024.
- *   fold_waves_per_cu, sweep_waves_per_cu   upper bound on the waves a compute unit holds at a
- *                             time, 1..32 (32 = no bound; defaults: 32 and 16).  Fewer requests in
- *                             flight keep DRAM rows open longer; enforced by reserving unused LDS.
+ *   fold_block, fused_block, sweep_block   threads per block of the per-bucket fold + sum-of-squares
+ *                             kernel (default: 1024 while a lane loads at most 64 bytes of views, else 128),
+ *                             of the per-bucket fold + optimizer kernel (default: 64 for launches under 2^27
+ *                             elements, else 128) and of the whole-arena optimizer sweep (default 256):
+ *                             64, 128, 256, 512 or 1024.
+ *   fold_waves_per_cu, fused_waves_per_cu, sweep_waves_per_cu   upper bound on the waves a compute
+ *                             unit holds of that kernel at a time, 1..32 (32 = no bound).  Defaults: no bound
+ *                             for 1024-thread fold blocks, else about 96 KiB of loads in flight per compute
+ *                             unit; about 80 KiB for the fold + optimizer kernel; never fewer than 8 waves;
+ *                             16 for the sweep.  Fewer requests in flight keep DRAM rows open longer; enforced
+ *                             by reserving unused LDS, in whole blocks and at most 64 KiB per block.
  *   max_launch_threads        a logical launch with more threads is issued as several launches
  *                             (default and upper limit 2^31; lower values exist so that tests can
  *                             reach the split paths with small inputs; at least one block and one
  *                             bucket go into every launch). */
 typedef struct {
     uint32_t fold_block;
+    uint32_t fused_block;
     uint32_t sweep_block;
     uint32_t fold_waves_per_cu;
+    uint32_t fused_waves_per_cu;
     uint32_t sweep_waves_per_cu;
     uint64_t max_launch_threads;
 } shadow_launch_shape;
@@ -337,9 +345,11 @@ int32_t shadow_ingest_bucket(shadow_ctx* ctx, uint32_t bucket_id, const void* co
  *   again, no separate copy pass and no wait for later iterations).  If
  *   h_dst_* (pinned host pointers, arena_numel floats each, all three NULL for
  *   none) are given, the staging set is drained to them on the copy stream
- *   from the boundary on, concurrently with every later iteration.  The
- *   staging set must not be read by the caller, and arm returns EBUSY, while a
- *   drain from it is still running.
+ *   from the boundary on, concurrently with every later iteration; arm
+ *   returns EBUSY while such a drain is still running (the staging set would be
+ *   overwritten under it).  Without host arrays the staging set itself is the
+ *   snapshot; arming again overwrites it, so a caller that reads it orders its
+ *   reads before the next arm.
  *
  * shadow_snapshot_record: records `event` (caller's hipEvent_t) behind the last
  *   requested snapshot (EBUSY while an armed snapshot's iteration is not yet

@@ -22,7 +22,19 @@ namespace {
 thread_local std::string g_hip_error;
 
 constexpr uint64_t kMaxThreadsPerLaunch = 1ull << 31;
-constexpr uint32_t kDefaultFoldBlock = 1024;     // threads per block of the per-bucket kernels
+// The fold + sum-of-squares kernel streams W arrays in and one out.  While a lane loads at most 64 bytes (W <= 8 bf16
+// views, or several narrow groups) 1024-thread blocks without a bound on the waves are fastest; with more bytes per
+// lane (W = 16, 32) 128-thread blocks and about 96 KiB of loads in flight per CU, but at least 8 waves (measured:
+// W = 16: 12 waves, -5 % time; W = 32: 8 waves, -4 %; fewer than 8 waves: +15 %).
+constexpr uint32_t kDefaultFoldBlock = 1024;
+constexpr uint32_t kWideFoldBlock = 128;
+constexpr uint32_t kFoldBytesInFlightPerCu = 96 * 1024;
+// The fold + optimizer kernel streams W + 3 arrays in and 3 out.  Measured on MI355X (sweeps of block size and of the
+// waves a CU holds, three model sizes, W = 1, 8, 16): it runs fastest with small blocks and with about 80 KiB of loads in
+// flight per CU, i.e. with FEWER waves the more bytes a lane loads (W = 16: 8 waves, W = 8: 10-12, W = 1: 16-24), but
+// never fewer than 8; launches under 2^27 elements prefer 64-thread blocks, longer ones 128-thread blocks.
+constexpr uint32_t kFusedBytesInFlightPerCu = 80 * 1024;
+constexpr uint64_t kFusedSmallLaunchElems = 1ull << 27;
 constexpr uint32_t kDefaultSweepBlock = 256;     // threads per block of the whole-arena optimizer sweep
 constexpr uint32_t kDefaultFoldWaves = 32;       // waves a CU may hold: no bound for the per-bucket kernels,
 constexpr uint32_t kDefaultSweepWaves = 16;      // 4 blocks of 256 threads for the sweep
@@ -99,7 +111,10 @@ struct shadow_ctx {
     double* d_partial = nullptr;
     double* d_stage1 = nullptr;
     uint32_t nstage1 = 0;
-    uint32_t fold_block = kDefaultFoldBlock, adamw_block = kDefaultSweepBlock, fold_lds = 0, adamw_lds = 0;
+    uint32_t fold_block = kDefaultFoldBlock, adamw_block = kDefaultSweepBlock;
+    uint32_t fold_lds = 0, adamw_lds = 0;
+    uint32_t fused_block_given = 0;       // 0: chosen per launch by its size
+    uint32_t fused_waves = 0;             // waves a CU may hold of the fold + optimizer kernel
     uint64_t max_launch_threads = kMaxThreadsPerLaunch;
     float* d_coef = nullptr;
     double* d_sumsq = nullptr;
@@ -123,7 +138,7 @@ struct shadow_ctx {
     bool armed = false, snap_active = false;   // armed: the next iteration also writes the staging set; active: this one does
     float* armed_host[3] = {nullptr, nullptr, nullptr};
     hipEvent_t drain_ev = nullptr;        // staging set has been drained (or simply completed) for the last armed snapshot
-    bool drain_recorded = false;
+    bool drain_recorded = false;          // drain_ev ends a drain to host arrays that may still be running
     bool have_snapshot = false;           // some snapshot was requested; last_snap_ev tells which event ends it
     hipEvent_t last_snap_ev = nullptr;
     uint64_t last_snap_step = 0;
@@ -248,10 +263,27 @@ uint32_t sumsq_vpl(const shadow_hparams& hp)
 }
 
 // blocks of a bucket's launch: update == false is the fold + sum-of-squares kernel
-uint32_t bucket_blocks(const shadow_ctx* c, uint64_t numel, bool update)
+// blocks of a bucket in the fold + sum-of-squares kernel
+uint32_t bucket_blocks(const shadow_ctx* c, uint64_t numel)
 {
-    const uint32_t vpl = update ? 1u : sumsq_vpl(c->hp);
-    return blocks_for(bucket_threads(numel), c->fold_block * vpl);
+    return blocks_for(bucket_threads(numel), c->fold_block * sumsq_vpl(c->hp));
+}
+
+// Launch shape of the fold + optimizer kernel for a launch list of total_elems elements.
+void fused_shape(const shadow_ctx* c, uint64_t total_elems, uint32_t* block, uint32_t* lds)
+{
+    *block = c->fused_block_given ? c->fused_block_given : (total_elems < kFusedSmallLaunchElems ? 64u : 128u);
+    uint32_t waves = c->fused_waves;
+    if (!waves) {
+        const uint32_t state_bytes = c->hp.optimizer == SHADOW_OPT_SGD ? 32u : 48u;
+        const uint32_t lane_bytes = kVec * c->lay.grad_elem_bytes * c->hp.num_workers + state_bytes;
+        const uint32_t wpb = *block / 64;
+        const double want = double(kFusedBytesInFlightPerCu) / (64.0 * lane_bytes);
+        waves = uint32_t(want / wpb + 0.5) * wpb;         // nearest whole number of blocks
+        if (waves < 8) waves = 8;
+        if (waves < wpb) waves = wpb;
+    }
+    *lds = lds_for_wave_cap(*block, waves);
 }
 
 int32_t get_event(shadow_ctx* c, hipEvent_t* out)
@@ -288,31 +320,33 @@ SnapSet snap_set(const shadow_ctx* c)
 }
 
 template <bool BF16, int W>
-void launch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map, bool update)
+void launch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map, bool update, uint32_t fused_block,
+                 uint32_t fused_lds)
 {
     const float* coef = c->clip ? c->d_coef : nullptr;
     const SnapSet sn = snap_set(c);
     if (!update)
         k_fold_sumsq<BF16, W><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->r, c->d_partial, c->sc);
     else if (c->hp.optimizer == SHADOW_OPT_ADAMW)
-        k_fold_adamw<BF16, W, kAdamW><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc, sn);
+        k_fold_adamw<BF16, W, kAdamW><<<grid, fused_block, fused_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc, sn);
     else if (c->hp.optimizer == SHADOW_OPT_ADAM)
-        k_fold_adamw<BF16, W, kAdam><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc, sn);
+        k_fold_adamw<BF16, W, kAdam><<<grid, fused_block, fused_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc, sn);
     else
-        k_fold_adamw<BF16, W, kSgd><<<grid, c->fold_block, c->fold_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc, sn);
+        k_fold_adamw<BF16, W, kSgd><<<grid, fused_block, fused_lds, st>>>(fb, c->p, c->m, c->v, coef, map, c->sc, sn);
 }
 
 template <bool BF16>
-void dispatch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map, bool update)
+void dispatch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map, bool update, uint32_t fblock,
+                   uint32_t flds)
 {
     switch (c->hp.num_workers) {
-        case 1: launch_fold<BF16, 1>(c, fb, grid, st, map, update); break;
-        case 2: launch_fold<BF16, 2>(c, fb, grid, st, map, update); break;
-        case 4: launch_fold<BF16, 4>(c, fb, grid, st, map, update); break;
-        case 8: launch_fold<BF16, 8>(c, fb, grid, st, map, update); break;
-        case 16: launch_fold<BF16, 16>(c, fb, grid, st, map, update); break;
-        case 32: launch_fold<BF16, 32>(c, fb, grid, st, map, update); break;
-        default: launch_fold<BF16, 0>(c, fb, grid, st, map, update);
+        case 1: launch_fold<BF16, 1>(c, fb, grid, st, map, update, fblock, flds); break;
+        case 2: launch_fold<BF16, 2>(c, fb, grid, st, map, update, fblock, flds); break;
+        case 4: launch_fold<BF16, 4>(c, fb, grid, st, map, update, fblock, flds); break;
+        case 8: launch_fold<BF16, 8>(c, fb, grid, st, map, update, fblock, flds); break;
+        case 16: launch_fold<BF16, 16>(c, fb, grid, st, map, update, fblock, flds); break;
+        case 32: launch_fold<BF16, 32>(c, fb, grid, st, map, update, fblock, flds); break;
+        default: launch_fold<BF16, 0>(c, fb, grid, st, map, update, fblock, flds);
     }
 }
 
@@ -359,6 +393,13 @@ int32_t launch_buckets(shadow_ctx* c, const uint32_t* ids, size_t count, PtrFn p
         const int32_t rc = wait_for_snapshot_copies(c, sid);
         if (rc != SHADOW_OK) return rc;
     }
+    uint32_t fblock = 0, flds = 0;
+    if (update) {
+        uint64_t total = 0;
+        for (size_t j = 0; j < count; ++j) total += c->lay.buckets[ids[j]].numel;
+        fused_shape(c, total, &fblock, &flds);
+    }
+    const uint32_t block = update ? fblock : c->fold_block;
     size_t i = 0;
     while (i < count) {
         FoldBatch fb{};
@@ -367,8 +408,8 @@ int32_t launch_buckets(shadow_ctx* c, const uint32_t* ids, size_t count, PtrFn p
         uint32_t k = 0;
         while (i < count && k < kMaxBatch && (k + 1) * W <= kMaxBatchPtrs) {
             const BucketL& b = c->lay.buckets[ids[i]];
-            const uint64_t nb = bucket_blocks(c, b.numel, update);
-            if (k > 0 && (blocks + nb) * c->fold_block > c->max_launch_threads) break;
+            const uint64_t nb = update ? blocks_for(bucket_threads(b.numel), block) : bucket_blocks(c, b.numel);
+            if (k > 0 && (blocks + nb) * block > c->max_launch_threads) break;
             fb.first_block[k] = uint32_t(blocks);
             fb.numel[k] = b.numel;
             fb.arena_off[k] = b.arena_off;
@@ -384,8 +425,8 @@ int32_t launch_buckets(shadow_ctx* c, const uint32_t* ids, size_t count, PtrFn p
         for (uint32_t j = k; j <= kMaxBatch; ++j) fb.first_block[j] = kNoBucket;   // "no bucket starts here"
         ProfScope ps(c, update ? SHADOW_K_FOLD_ADAMW : SHADOW_K_FOLD_SUMSQ, st);
         if (ps.rc != SHADOW_OK) return ps.rc;
-        if (c->hp.grad_dtype == SHADOW_GRAD_BF16) dispatch_fold<true>(c, fb, grid, st, map, update);
-        else dispatch_fold<false>(c, fb, grid, st, map, update);
+        if (c->hp.grad_dtype == SHADOW_GRAD_BF16) dispatch_fold<true>(c, fb, grid, st, map, update, fblock, flds);
+        else dispatch_fold<false>(c, fb, grid, st, map, update, fblock, flds);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             g_hip_error = std::string("fold kernel launch: ") + hipGetErrorString(e);
@@ -472,7 +513,7 @@ bool assign_slots(shadow_ctx* c)
     uint64_t total = 0;
     for (size_t b = 0; b < L.buckets.size(); ++b) {
         c->slot_base[b] = uint32_t(total);
-        c->slot_count[b] = bucket_blocks(c, L.buckets[b].numel, false) * (c->fold_block / 64);
+        c->slot_count[b] = bucket_blocks(c, L.buckets[b].numel) * (c->fold_block / 64);
         total += c->slot_count[b];
         if (total > 0x7FFFFFFFull) return false;
     }
@@ -720,8 +761,11 @@ int32_t check_replica_args(const shadow_layout* layout, const shadow_hparams* hp
     if (hp->reduce_op != SHADOW_REDUCE_MEAN && hp->reduce_op != SHADOW_REDUCE_SUM) return SHADOW_EINVAL;
     if (hp->num_streams < 1 || hp->num_streams > SHADOW_MAX_STREAMS) return SHADOW_EINVAL;
     const shadow_launch_shape& ls = hp->launch;
-    if ((ls.fold_block && !valid_block(ls.fold_block)) || (ls.sweep_block && !valid_block(ls.sweep_block))) return SHADOW_EINVAL;
-    if (ls.fold_waves_per_cu > 32 || ls.sweep_waves_per_cu > 32 || ls.max_launch_threads > kMaxThreadsPerLaunch) return SHADOW_EINVAL;
+    if ((ls.fold_block && !valid_block(ls.fold_block)) || (ls.fused_block && !valid_block(ls.fused_block)) ||
+        (ls.sweep_block && !valid_block(ls.sweep_block)))
+        return SHADOW_EINVAL;
+    if (ls.fold_waves_per_cu > 32 || ls.fused_waves_per_cu > 32 || ls.sweep_waves_per_cu > 32 || ls.max_launch_threads > kMaxThreadsPerLaunch)
+        return SHADOW_EINVAL;
     const bool clip = hp->max_grad_norm > 0.f;
     if (!clip && d_reduced) return SHADOW_EINVAL;
     if (!aligned(d_param, 256) || !aligned(d_m, 256) || !aligned(d_v, 256) || !aligned(d_reduced, 256)) return SHADOW_EINVAL;
@@ -735,9 +779,23 @@ int32_t check_replica_args(const shadow_layout* layout, const shadow_hparams* hp
 // Launch shape of a context from the hyper-parameters (zero fields take the defaults).
 void set_launch_shape(shadow_ctx* c, const shadow_launch_shape& ls)
 {
-    c->fold_block = ls.fold_block ? ls.fold_block : kDefaultFoldBlock;
+    const uint32_t fold_lane_bytes = kVec * c->lay.grad_elem_bytes * c->hp.num_workers * sumsq_vpl(c->hp);
+    const bool wide = fold_lane_bytes > 64;
+    c->fold_block = ls.fold_block ? ls.fold_block : (wide ? kWideFoldBlock : kDefaultFoldBlock);
+    uint32_t fold_waves = ls.fold_waves_per_cu;
+    if (!fold_waves) {
+        fold_waves = kDefaultFoldWaves;
+        if (wide) {
+            const uint32_t wpb = c->fold_block / 64;
+            fold_waves = uint32_t(double(kFoldBytesInFlightPerCu) / (64.0 * fold_lane_bytes) / wpb + 0.5) * wpb;
+            if (fold_waves < 8) fold_waves = 8;
+            if (fold_waves < wpb) fold_waves = wpb;
+        }
+    }
+    c->fused_block_given = ls.fused_block;
+    c->fused_waves = ls.fused_waves_per_cu;
     c->adamw_block = ls.sweep_block ? ls.sweep_block : kDefaultSweepBlock;
-    c->fold_lds = lds_for_wave_cap(c->fold_block, ls.fold_waves_per_cu ? ls.fold_waves_per_cu : kDefaultFoldWaves);
+    c->fold_lds = lds_for_wave_cap(c->fold_block, fold_waves);
     c->adamw_lds = lds_for_wave_cap(c->adamw_block, ls.sweep_waves_per_cu ? ls.sweep_waves_per_cu : kDefaultSweepWaves);
     c->max_launch_threads = ls.max_launch_threads ? ls.max_launch_threads : kMaxThreadsPerLaunch;
 }
@@ -845,7 +903,7 @@ int32_t finish_armed_snapshot(shadow_ctx* c, uint64_t step)
     if (c->armed_host[2] && c->stage_v) HIP_TRY(hipMemcpyAsync(c->armed_host[2], c->stage_v, bytes, hipMemcpyDeviceToHost, c->snap_stream));
     if (ps.end() != SHADOW_OK) return SHADOW_EHIP;
     HIP_TRY(hipEventRecord(c->drain_ev, c->snap_stream));
-    c->drain_recorded = true;
+    c->drain_recorded = c->armed_host[0] || c->armed_host[1] || (c->armed_host[2] && c->stage_v);
     c->snap_active = false;
     c->have_snapshot = true;
     c->last_snap_ev = c->drain_ev;

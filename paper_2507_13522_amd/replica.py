@@ -91,7 +91,8 @@ class GpuShadow:
     def __init__(self, wl, inputs, num_streams: int = 2, mean: bool = True, torch_streams: bool = False,
                  resident_grads: bool = True, init_from=None, start_step: int = 0, advised_placement: bool = True,
                  batch_bytes: int = 0, refold: bool = False, optimizer: str = "adamw", ring_bytes: int = 0,
-                 placement: Optional[str] = None, snapshot_set: bool = False, launch: Optional[sh.LaunchShape] = None):
+                 placement: Optional[str] = None, snapshot_set: bool = False, launch: Optional[sh.LaunchShape] = None,
+                 attach_snapshot_set: bool = True):
         assert torch.cuda.is_available()
         self.wl, self.inputs = wl, inputs
         self.dev = torch.device("cuda:0")
@@ -150,7 +151,7 @@ class GpuShadow:
         self.ctx = sh.Shadow(L, self.hp, self.p.data_ptr(), self.m.data_ptr(), None if optimizer == "sgd" else self.v.data_ptr(),
                              self.r.data_ptr() if self.r is not None else None, start_step,
                              [s.cuda_stream for s in self._tstreams] if self._tstreams else None)
-        if self.snap is not None:
+        if self.snap is not None and attach_snapshot_set:
             self.ctx.snapshot_attach(self.snap[0].data_ptr(), self.snap[1].data_ptr(),
                                      None if optimizer == "sgd" else self.snap[2].data_ptr())
         self._views = None

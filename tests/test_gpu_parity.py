@@ -578,8 +578,8 @@ def test_logical_launches_split_into_several(W, dtype, clip, refold):
     nthreads = sum(n for n, _ in RAGGED) // 4
     for limit, fold_block, sweep_block in ((4096, 1024, 256), (1000, 256, 64), (1 << 16, 512, 1024)):
         assert nthreads // limit >= 1
-        launch = sh.LaunchShape(fold_block=fold_block, sweep_block=sweep_block, max_launch_threads=limit,
-                                fold_waves_per_cu=16, sweep_waves_per_cu=8)
+        launch = sh.LaunchShape(fold_block=fold_block, fused_block=fold_block // 2, sweep_block=sweep_block, max_launch_threads=limit,
+                                fold_waves_per_cu=16, fused_waves_per_cu=12, sweep_waves_per_cu=8)
         check_against_oracle(wl, num_streams=2, batch_bytes=1 << 62, refold=refold, launch=launch)
     n = 3_000_000
     src = torch.randint(0, 255, (n * 16,), dtype=torch.uint8, device="cuda:0")

@@ -97,7 +97,7 @@ def test_init_validates_before_touching_the_gpu():
     bad = [dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0), dict(lr=-1.0), dict(num_workers=0), dict(num_workers=65),
            dict(grad_dtype=7), dict(grad_dtype=sh.GRAD_F32), dict(reduce_op=3), dict(num_streams=0), dict(num_streams=17),
            dict(weight_decay=-1.0), dict(launch=sh.LaunchShape(fold_block=96)), dict(launch=sh.LaunchShape(sweep_block=2048)),
-           dict(launch=sh.LaunchShape(sweep_waves_per_cu=33)), dict(launch=sh.LaunchShape(max_launch_threads=(1 << 31) + 1))]
+           dict(launch=sh.LaunchShape(sweep_waves_per_cu=33)), dict(launch=sh.LaunchShape(fused_waves_per_cu=40)), dict(launch=sh.LaunchShape(max_launch_threads=(1 << 31) + 1))]
     for kw in bad:
         hp = sh.HParams(**{**good, **kw})
         with pytest.raises(sh.ShadowError) as e:
