@@ -25,22 +25,23 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 
 # HBM bytes per launch of the roofline kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file with
 # its defaults (profiles/*_bench_rocprofv3.md), each counter scaled by what it reads for the library's plain copy
-# kernel over 1 GiB.  Keyed by (workload, kernel, --refold); only reported for default settings and while the
-# kernel sources still hash to the value the counters were taken at.
-MEASURED_TRAFFIC_SOURCES_SHA256 = "6ffb520511c7e7820db9efbebc8bd52e2c3a42b1c7737e6433e1c8818c0c9051"
+# kernel over 1 GiB.  Keyed by (workload, kernel, --refold, --no-clip); only reported for default settings and while
+# the kernel sources still hash to the value the counters were taken at.
+MEASURED_TRAFFIC_SOURCES_SHA256 = "f915f9a7b09a55b6935f490dc0b9dc3fb3f8272805ec9ef46c0869196195b42b"
 MEASURED_TRAFFIC = {
-    ("llama7b", "k_adamw", False): 188702813973.3,
-    ("ragged7b", "k_fold_sumsq", False): 5667041614.3,
-    ("gpt1p3b", "k_fold_sumsq", False): 4740532596.9,
-    ("llama7b_w1", "k_fold_adamw", True): 21901912418.0,
-    ("gpt2s", "k_fold_adamw", False): 4978171250.5,
+    ("llama7b", "k_adamw", False, False): 188701134326.7,
+    ("ragged7b", "k_fold_sumsq", False, False): 5669629383.3,
+    ("gpt1p3b", "k_fold_sumsq", False, False): 4744684467.9,
+    ("llama7b_w1", "k_fold_adamw", True, False): 21902630125.4,
+    ("gpt2s", "k_fold_adamw", False, False): 4978099181.8,
+    ("llama7b", "k_fold_adamw", False, True): 11231576737.6,
 }
 KERNEL_SOURCES = ("paper_2507_13522_amd/csrc/shadow_kernels.hip.h", "paper_2507_13522_amd/csrc/shadow.hip")
 
 
-def measured_traffic(workload: str, kernel: str, refold: bool, defaults: bool):
+def measured_traffic(workload: str, kernel: str, refold: bool, noclip: bool, defaults: bool):
     import hashlib
-    rec = MEASURED_TRAFFIC.get((workload, kernel, refold))
+    rec = MEASURED_TRAFFIC.get((workload, kernel, refold, noclip))
     if rec is None or not defaults:
         return None
     h = hashlib.sha256()
@@ -52,7 +53,7 @@ def measured_traffic(workload: str, kernel: str, refold: bool, defaults: bool):
 
 VIEW_RING_BYTES = 96 << 30       # ring of gradient views for workloads whose views do not all fit in HBM
 
-KERNEL_NAMES = {0: "k_fold_adamw", 1: "k_fold_sumsq", 2: "k_norm_finalize", 3: "k_adamw"}
+KERNEL_NAMES = {0: "k_fold_adamw", 1: "k_fold_sumsq", 2: "k_norm_finalize", 3: "k_adamw", 4: "snapshot_copies"}
 
 
 def algorithmic_bytes_per_param(wl, refold: bool = False, optimizer: str = "adamw") -> dict:
@@ -161,8 +162,11 @@ def main() -> int:
     ap.add_argument("--fold-waves", type=int, default=0, help="upper bound on the waves per CU of the fold + sum-of-squares kernel")
     ap.add_argument("--fused-waves", type=int, default=0, help="upper bound on the waves per CU of the fold + optimizer kernel")
     ap.add_argument("--sweep-waves", type=int, default=0, help="upper bound on the waves per CU of the optimizer sweep")
+    ap.add_argument("--drain-blocks", type=int, default=0, help="blocks of the kernel that drains a snapshot to the host")
     ap.add_argument("--placement", default="auto", choices=["auto", "plan", "stride", "separate"],
                     help="where the arenas and views lie in HBM (auto: the library's device plan, else its stride advice)")
+    ap.add_argument("--offsets-gib", default=None,
+                    help="placement experiments: GiB offsets 'param,m,v,scratch,staging' inside one 256 GiB allocation")
     ap.add_argument("--snapshot-every", type=int, default=0,
                     help="take a snapshot of the replica every N-th timed iteration (0 = never)")
     ap.add_argument("--snapshot-mode", default="staged", choices=["staged", "copy"],
@@ -192,13 +196,13 @@ def main() -> int:
 
     default_settings = (args.streams is None and args.batch_mib is None and args.optimizer == "adamw" and not args.ingest_slots
                         and not args.fold_block and not args.fused_block and not args.sweep_block and not args.fold_waves and not args.fused_waves and not args.sweep_waves
-                        and args.placement == "auto" and not args.snapshot_every and not args.view_ring_gib and not args.no_clip)
+                        and args.placement == "auto" and not args.offsets_gib and not args.snapshot_every and not args.view_ring_gib)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     launch = sh.LaunchShape(fold_block=args.fold_block, fused_block=args.fused_block, sweep_block=args.sweep_block, fold_waves_per_cu=args.fold_waves,
-                            fused_waves_per_cu=args.fused_waves, sweep_waves_per_cu=args.sweep_waves)
+                            fused_waves_per_cu=args.fused_waves, sweep_waves_per_cu=args.sweep_waves, drain_blocks=args.drain_blocks)
 
     wl = synth.get_workload(args.workload)
     if args.no_clip:
@@ -216,14 +220,18 @@ def main() -> int:
         if state_bytes + lay.staging_bytes(wl.num_workers) > (250 << 30):
             ring_bytes = VIEW_RING_BYTES if not snapshots else 32 << 30
         lay.close()
+    offsets = None
+    if args.offsets_gib:
+        vals = [int(float(x) * (1 << 30)) for x in args.offsets_gib.split(",")]
+        offsets = dict(zip(("param", "m", "v", "scratch", "staging"), vals))
     g = GpuShadow(wl, inputs, num_streams=streams, batch_bytes=batch_bytes, refold=args.refold, optimizer=args.optimizer,
-                  resident_grads=not ingest, ring_bytes=ring_bytes, placement=args.placement,
+                  resident_grads=not ingest, ring_bytes=ring_bytes, placement="explicit" if offsets else args.placement, offsets=offsets,
                   snapshot_set=staged or (snapshots and not args.snapshot_host), attach_snapshot_set=staged, launch=launch)
     P = g.layout.num_params
     A = g.layout.arena_numel
     snap_dev = snap_host = None
     if snapshots and args.snapshot_host:
-        snap_host = [torch.empty(A, dtype=torch.float32).pin_memory() for _ in range(3)]
+        snap_host = [torch.empty(A, dtype=torch.float32, pin_memory=True) for _ in range(3)]
     elif snapshots and not staged:
         snap_dev = g.snap                      # a second set of arenas, placed with everything else
     snap_taken, snap_skipped = 0, 0
@@ -341,11 +349,11 @@ def main() -> int:
     achieved = bytes_per_launch / (kernels[dom]["avg_ms"] * 1e-3) / 1e9
     total_gbs = bpp["total"] * P / (ms_per_step * 1e-3) / 1e9
 
-    traffic = measured_traffic(wl.name, dom, bool(args.refold), default_settings and g.placement == "plan")
+    traffic = measured_traffic(wl.name, dom, bool(args.refold), bool(args.no_clip), default_settings and g.placement == "plan")
     traffic_source = None
     if traffic is not None:
         traffic_source = (f"stored, not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, "
-                          f"profiles/{wl.name}{'_refold' if args.refold else ''}_bench_rocprofv3.md, "
+                          f"profiles/{wl.name}{'_refold' if args.refold else ''}{'_noclip' if args.no_clip else ''}_bench_rocprofv3.md, "
                           f"taken at kernel sources sha256 {MEASURED_TRAFFIC_SOURCES_SHA256[:16]}")
     out = {
         "metric": "shadow update params/sec and achieved HBM GB/s (% of peak) per iteration",
@@ -370,6 +378,7 @@ def main() -> int:
                    "grad_dtype": wl.grad_dtype, "streams": streams,
                    "batch_bytes": batch_bytes, "refold": bool(args.refold), "optimizer": args.optimizer,
                    "ingest_slots": args.ingest_slots, "view_ring_bytes": ring_bytes, "placement": g.placement,
+                   "offsets_gib": args.offsets_gib,
                    "snapshot_every": args.snapshot_every, "snapshot_mode": args.snapshot_mode if snapshots else None,
                    "snapshot_to_host": bool(snapshots and args.snapshot_host)},
         "hbm_GBps": total_gbs,
@@ -383,7 +392,11 @@ def main() -> int:
                      "bytes_per_launch": bytes_per_launch, "avg_launch_ms": kernels[dom]["avg_ms"]},
     }
     if snapshots:
+        sc = kernels.get("snapshot_copies")
+        nbytes = A * 4 * (2 if args.optimizer == "sgd" else 3)
         out["snapshots"] = {"taken": snap_taken, "skipped_while_draining": snap_skipped,
+                            "copy_ms_each": sc["avg_ms"] if sc else None,
+                            "copy_GBps": (nbytes / (sc["avg_ms"] * 1e-3) / 1e9) if sc and (args.snapshot_host or not staged) else None,
                             "ms_per_step_updates_only": 1e3 * t_updates / args.steps,
                             "extra_bytes_per_param_on_a_snapshot_step": 12 if staged else 24}
     g.close()

@@ -81,6 +81,11 @@ typedef struct {
  *                             unit; about 80 KiB for the fold + optimizer kernel; never fewer than 8 waves;
  *                             16 for the sweep.  Fewer requests in flight keep DRAM rows open longer; enforced
  *                             by reserving unused LDS, in whole blocks and at most 64 KiB per block.
+ *   drain_blocks              256-thread blocks of the kernel that writes a snapshot to pinned host
+ *                             memory (default 4, at most 4096): few on purpose.  Measured: once the stores
+ *                             to the host saturate the link (8 blocks and more, and the runtime's own
+ *                             device-to-host copy kernel) every kernel that runs beside them slows by
+ *                             50-100 %; at 1-4 blocks (10-25 GB/s to the host) by 3-6 %.
  *   max_launch_threads        a logical launch with more threads is issued as several launches
  *                             (default and upper limit 2^31; lower values exist so that tests can
  *                             reach the split paths with small inputs; at least one block and one
@@ -92,6 +97,8 @@ typedef struct {
     uint32_t fold_waves_per_cu;
     uint32_t fused_waves_per_cu;
     uint32_t sweep_waves_per_cu;
+    uint32_t drain_blocks;
+    uint32_t reserved;          /* must be 0 */
     uint64_t max_launch_threads;
 } shadow_launch_shape;
 
@@ -345,7 +352,9 @@ int32_t shadow_ingest_bucket(shadow_ctx* ctx, uint32_t bucket_id, const void* co
  *   again, no separate copy pass and no wait for later iterations).  If
  *   h_dst_* (pinned host pointers, arena_numel floats each, all three NULL for
  *   none) are given, the staging set is drained to them on the copy stream
- *   from the boundary on, concurrently with every later iteration; arm
+ *   from the boundary on, concurrently with every later iteration (by a copy
+ *   kernel of a few blocks, see drain_blocks, which leaves the chip to the
+ *   update kernels); arm
  *   returns EBUSY while such a drain is still running (the staging set would be
  *   overwritten under it).  Without host arrays the staging set itself is the
  *   snapshot; arming again overwrites it, so a caller that reads it orders its

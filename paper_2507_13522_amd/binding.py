@@ -30,7 +30,7 @@ class LaunchShape(C.Structure):
     """shadow_launch_shape: every field 0 = the library's default."""
     _fields_ = [("fold_block", C.c_uint32), ("fused_block", C.c_uint32), ("sweep_block", C.c_uint32),
                 ("fold_waves_per_cu", C.c_uint32), ("fused_waves_per_cu", C.c_uint32), ("sweep_waves_per_cu", C.c_uint32),
-                ("max_launch_threads", C.c_uint64)]
+                ("drain_blocks", C.c_uint32), ("reserved", C.c_uint32), ("max_launch_threads", C.c_uint64)]
 
 
 class HParams(C.Structure):

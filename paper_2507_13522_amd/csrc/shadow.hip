@@ -38,6 +38,7 @@ constexpr uint64_t kFusedSmallLaunchElems = 1ull << 27;
 constexpr uint32_t kDefaultSweepBlock = 256;     // threads per block of the whole-arena optimizer sweep
 constexpr uint32_t kDefaultFoldWaves = 32;       // waves a CU may hold: no bound for the per-bucket kernels,
 constexpr uint32_t kDefaultSweepWaves = 16;      // 4 blocks of 256 threads for the sweep
+constexpr uint32_t kDefaultDrainBlocks = 4;      // blocks of the kernel that drains a snapshot to the host
 constexpr uint32_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxSpansPerKind = 65536;
 
@@ -115,6 +116,7 @@ struct shadow_ctx {
     uint32_t fold_lds = 0, adamw_lds = 0;
     uint32_t fused_block_given = 0;       // 0: chosen per launch by its size
     uint32_t fused_waves = 0;             // waves a CU may hold of the fold + optimizer kernel
+    uint32_t drain_blocks = kDefaultDrainBlocks;
     uint64_t max_launch_threads = kMaxThreadsPerLaunch;
     float* d_coef = nullptr;
     double* d_sumsq = nullptr;
@@ -764,7 +766,8 @@ int32_t check_replica_args(const shadow_layout* layout, const shadow_hparams* hp
     if ((ls.fold_block && !valid_block(ls.fold_block)) || (ls.fused_block && !valid_block(ls.fused_block)) ||
         (ls.sweep_block && !valid_block(ls.sweep_block)))
         return SHADOW_EINVAL;
-    if (ls.fold_waves_per_cu > 32 || ls.fused_waves_per_cu > 32 || ls.sweep_waves_per_cu > 32 || ls.max_launch_threads > kMaxThreadsPerLaunch)
+    if (ls.fold_waves_per_cu > 32 || ls.fused_waves_per_cu > 32 || ls.sweep_waves_per_cu > 32 || ls.drain_blocks > 4096 || ls.reserved != 0 ||
+        ls.max_launch_threads > kMaxThreadsPerLaunch)
         return SHADOW_EINVAL;
     const bool clip = hp->max_grad_norm > 0.f;
     if (!clip && d_reduced) return SHADOW_EINVAL;
@@ -794,6 +797,7 @@ void set_launch_shape(shadow_ctx* c, const shadow_launch_shape& ls)
     }
     c->fused_block_given = ls.fused_block;
     c->fused_waves = ls.fused_waves_per_cu;
+    c->drain_blocks = ls.drain_blocks ? ls.drain_blocks : kDefaultDrainBlocks;
     c->adamw_block = ls.sweep_block ? ls.sweep_block : kDefaultSweepBlock;
     c->fold_lds = lds_for_wave_cap(c->fold_block, fold_waves);
     c->adamw_lds = lds_for_wave_cap(c->adamw_block, ls.sweep_waves_per_cu ? ls.sweep_waves_per_cu : kDefaultSweepWaves);
@@ -887,6 +891,24 @@ int32_t precheck_bucket(const shadow_ctx* c, uint32_t bucket_id, const void* con
     return SHADOW_OK;
 }
 
+// One array of the replica (or of the staging set) to a snapshot destination, on the copy stream.  Pinned host
+// memory is written by the small drain kernel through its device-side mapping; device memory (and host memory the
+// device cannot address) by the runtime's copy.
+int32_t snapshot_copy(shadow_ctx* c, float* dst, const float* src, size_t bytes)
+{
+    hipPointerAttribute_t attr{};
+    void* mapped = nullptr;
+    if (hipPointerGetAttributes(&attr, dst) == hipSuccess && attr.type == hipMemoryTypeHost &&
+        hipHostGetDevicePointer(&mapped, dst, 0) == hipSuccess && mapped && aligned(mapped, 16) && bytes % 16 == 0) {
+        k_drain<<<c->drain_blocks, 256, 0, c->snap_stream>>>(reinterpret_cast<const u32x4*>(src), static_cast<u32x4*>(mapped), bytes >> 4);
+        HIP_TRY(hipGetLastError());
+        return SHADOW_OK;
+    }
+    (void)hipGetLastError();          // a pointer the runtime does not know leaves an error behind: not ours
+    HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, c->snap_stream));
+    return SHADOW_OK;
+}
+
 // The iteration that just completed was armed: its update kernels wrote the staging set as well.
 // Order the copy stream behind them and drain the staging set to the host arrays, if any were given.
 int32_t finish_armed_snapshot(shadow_ctx* c, uint64_t step)
@@ -898,9 +920,9 @@ int32_t finish_armed_snapshot(shadow_ctx* c, uint64_t step)
     const size_t bytes = c->lay.arena_numel * sizeof(float);
     ProfScope ps(c, SHADOW_K_SNAPSHOT, c->snap_stream);
     if (ps.rc != SHADOW_OK) return ps.rc;
-    if (c->armed_host[0]) HIP_TRY(hipMemcpyAsync(c->armed_host[0], c->stage_p, bytes, hipMemcpyDeviceToHost, c->snap_stream));
-    if (c->armed_host[1]) HIP_TRY(hipMemcpyAsync(c->armed_host[1], c->stage_m, bytes, hipMemcpyDeviceToHost, c->snap_stream));
-    if (c->armed_host[2] && c->stage_v) HIP_TRY(hipMemcpyAsync(c->armed_host[2], c->stage_v, bytes, hipMemcpyDeviceToHost, c->snap_stream));
+    if (c->armed_host[0] && (rc = snapshot_copy(c, c->armed_host[0], c->stage_p, bytes)) != SHADOW_OK) return rc;
+    if (c->armed_host[1] && (rc = snapshot_copy(c, c->armed_host[1], c->stage_m, bytes)) != SHADOW_OK) return rc;
+    if (c->armed_host[2] && c->stage_v && (rc = snapshot_copy(c, c->armed_host[2], c->stage_v, bytes)) != SHADOW_OK) return rc;
     if (ps.end() != SHADOW_OK) return SHADOW_EHIP;
     HIP_TRY(hipEventRecord(c->drain_ev, c->snap_stream));
     c->drain_recorded = c->armed_host[0] || c->armed_host[1] || (c->armed_host[2] && c->stage_v);
@@ -1169,15 +1191,16 @@ int32_t shadow_snapshot(shadow_ctx* c, float* dst_param, float* dst_m, float* ds
     const size_t bytes = c->lay.arena_numel * sizeof(float);
     ProfScope ps(c, SHADOW_K_SNAPSHOT, c->snap_stream);
     if (ps.rc != SHADOW_OK) return ps.rc;
-    hipError_t e = hipSuccess;
-    if (dst_param) e = hipMemcpyAsync(dst_param, c->p, bytes, hipMemcpyDefault, c->snap_stream);
-    if (e == hipSuccess && dst_m) e = hipMemcpyAsync(dst_m, c->m, bytes, hipMemcpyDefault, c->snap_stream);
-    if (e == hipSuccess && dst_v && c->v) e = hipMemcpyAsync(dst_v, c->v, bytes, hipMemcpyDefault, c->snap_stream);
+    int32_t rcopy = SHADOW_OK;
+    if (dst_param) rcopy = snapshot_copy(c, dst_param, c->p, bytes);
+    if (rcopy == SHADOW_OK && dst_m) rcopy = snapshot_copy(c, dst_m, c->m, bytes);
+    if (rcopy == SHADOW_OK && dst_v && c->v) rcopy = snapshot_copy(c, dst_v, c->v, bytes);
     // whatever was enqueued, later writers of the replica must stay behind it
     const hipError_t e2 = hipEventRecord(c->snap_ev, c->snap_stream);
     std::fill(c->snap_wait.begin(), c->snap_wait.end(), uint8_t(1));
-    if (e != hipSuccess || e2 != hipSuccess) {
-        g_hip_error = std::string("snapshot copy: ") + hipGetErrorString(e != hipSuccess ? e : e2);
+    if (rcopy != SHADOW_OK) return poison(rcopy);
+    if (e2 != hipSuccess) {
+        g_hip_error = std::string("hipEventRecord: ") + hipGetErrorString(e2);
         return poison(SHADOW_EHIP);
     }
     if (ps.end() != SHADOW_OK) return poison(SHADOW_EHIP);

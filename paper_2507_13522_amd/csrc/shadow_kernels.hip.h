@@ -551,6 +551,29 @@ __global__ __launch_bounds__(kMaxBlock) void k_copy(const u32x4* __restrict__ sr
     if (i < n16) store_once(dst + i, load_once(src + i));
 }
 
+// ---- kernel: drain a snapshot to host memory at a bounded rate --------------------------
+// dst is pinned host memory mapped into the device's address space.  The grid is a handful of
+// blocks on purpose.  Measured on MI355X: while stores to the host saturate the link (this
+// kernel with 8 blocks or more, and equally the runtime's own device-to-host copy kernel), every
+// kernel that runs beside them takes 1.5 to 2 times as long, although the link carries under
+// 1 % of the HBM rate; with 1 to 4 blocks (10-25 GB/s to the host) the others lose 3-6 %.
+// Every lane walks the array with the grid's stride, four vectors in flight, until it is past
+// the end.
+__global__ __launch_bounds__(256) void k_drain(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n16)
+{
+    const uint64_t stride = uint64_t(gridDim.x) * blockDim.x;
+    uint64_t i = uint64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 a = load_once(src + i), b = load_once(src + i + stride), c = load_once(src + i + 2 * stride),
+                    d = load_once(src + i + 3 * stride);
+        dst[i] = a;
+        dst[i + stride] = b;
+        dst[i + 2 * stride] = c;
+        dst[i + 3 * stride] = d;
+    }
+    for (; i < n16; i += stride) dst[i] = load_once(src + i);
+}
+
 // ---- kernels: weight-decay tables written on the device (no host-to-device copy) ---------
 // A chunk of the run table travels in the kernel arguments and is written to its place.
 constexpr int kRunChunk = 256;

@@ -10,6 +10,7 @@ library's kernels.  Placement follows the library's advice (``shadow_layout_devi
     "stride"    the arenas carved from one allocation, a power-of-two stride apart; views separate
     "separate"  every arena an allocation of its own, wherever the allocator puts it
     "packed"    the arenas back to back in one allocation (small test cases)
+    "explicit"  ONE allocation of 256 GiB, byte offsets given by the caller (placement experiments)
 
 ``placement="auto"`` asks for the plan when the arenas reach 256 MiB and falls back to "stride" when
 the plan does not fit or the block cannot be allocated; ``Memory.placement`` names what was used.
@@ -33,7 +34,8 @@ class Memory:
     """p, m, v, the scratch arena r (or None), the views' staging buffer (or None) and the snapshot set (or None)."""
 
     def __init__(self, layout: sh.Layout, with_scratch: bool, staging_bytes: int, with_snapshot_set: bool = False,
-                 placement: str = "auto", device: str = "cuda:0"):
+                 placement: str = "auto", device: str = "cuda:0", offsets: Optional[dict] = None):
+        """offsets (placement "explicit"): byte offsets {"param", "m", "v", "scratch", "staging"} inside a 256 GiB block."""
         dev = torch.device(device)
         A = layout.arena_numel
         narr = 4 if with_scratch else 3
@@ -44,6 +46,18 @@ class Memory:
         self.stage = None
         self.snap = None
         arenas: List[torch.Tensor] = []
+        if want == "explicit":
+            assert offsets is not None and not with_snapshot_set
+            self.block = torch.empty(256 << 30, dtype=torch.uint8, device=dev)
+            cut = lambda o: self.block[o:o + A * 4].view(torch.float32)
+            arenas = [cut(offsets["param"]), cut(offsets["m"]), cut(offsets["v"])]
+            if with_scratch:
+                arenas.append(cut(offsets["scratch"]))
+            if staging_bytes:
+                self.stage = self.block[offsets["staging"]:offsets["staging"] + staging_bytes]
+            spans = sorted([(offsets[k], A * 4) for k in ("param", "m", "v")] + ([(offsets["scratch"], A * 4)] if with_scratch else [])
+                           + ([(offsets["staging"], staging_bytes)] if staging_bytes else []))
+            assert all(a + n <= b for (a, n), (b, _) in zip(spans, spans[1:])) and spans[-1][0] + spans[-1][1] <= (256 << 30), "parts overlap"
         if want == "plan":
             plan = layout.device_plan(with_scratch, staging_bytes, with_snapshot_set)
             if plan is not None:
@@ -69,7 +83,7 @@ class Memory:
             arenas = [self.block[k * stride:k * stride + A * 4].view(torch.float32) for k in range(narr)]
         elif want == "separate":
             arenas = [torch.empty(A, dtype=torch.float32, device=dev) for _ in range(narr)]
-        elif want != "plan":
+        elif want not in ("plan", "explicit"):
             raise ValueError(f"placement {placement!r}")
         if staging_bytes and self.stage is None:
             self.stage = torch.empty(staging_bytes, dtype=torch.uint8, device=dev)
@@ -92,7 +106,7 @@ class GpuShadow:
                  resident_grads: bool = True, init_from=None, start_step: int = 0, advised_placement: bool = True,
                  batch_bytes: int = 0, refold: bool = False, optimizer: str = "adamw", ring_bytes: int = 0,
                  placement: Optional[str] = None, snapshot_set: bool = False, launch: Optional[sh.LaunchShape] = None,
-                 attach_snapshot_set: bool = True):
+                 attach_snapshot_set: bool = True, offsets: Optional[dict] = None):
         assert torch.cuda.is_available()
         self.wl, self.inputs = wl, inputs
         self.dev = torch.device("cuda:0")
@@ -124,7 +138,7 @@ class GpuShadow:
             stage_bytes = ring_bytes
         if placement is None:
             placement = "auto" if advised_placement else "packed"
-        self.mem = Memory(L, clip and not refold, stage_bytes, snapshot_set, placement, "cuda:0")
+        self.mem = Memory(L, clip and not refold, stage_bytes, snapshot_set, placement, "cuda:0", offsets)
         self.placement = self.mem.placement
         self.p, self.m, self.v, self.r = self.mem.p, self.mem.m, self.mem.v, self.mem.r
         self._stage = self.mem.stage

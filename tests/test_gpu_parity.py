@@ -447,6 +447,28 @@ def test_snapshot_orders_before_next_iteration(clip, streams, batch_bytes):
     g.close()
 
 
+def test_snapshot_destinations_device_pinned_and_pageable():
+    """Pinned host memory is written by the library's drain kernel, device memory and pageable host memory by the
+    runtime's copy; all three hold the same state."""
+    say("case snapshot destinations")
+    wl = custom("snap-dst", RAGGED, 2, "bf16", clip=0.01, cap=200_000, steps=2)
+    g = GpuShadow(wl, Inputs(wl), num_streams=2, launch=sh.LaunchShape(drain_blocks=3))
+    A = g.layout.arena_numel
+    g.run_step(1)
+    dev = [torch.empty(A, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    pinned = [torch.empty(A, dtype=torch.float32, pin_memory=True) for _ in range(3)]
+    pageable = [torch.empty(A, dtype=torch.float32) for _ in range(3)]
+    inner = torch.empty(3 * A + 64, dtype=torch.float32, pin_memory=True)        # destinations inside a larger pinned block
+    inside = [inner[64 + k * A:64 + (k + 1) * A] for k in range(3)]
+    for dst in (dev, pinned, pageable, inside):
+        assert g.ctx.snapshot(*(d.data_ptr() for d in dst)) == 1
+    assert g.ctx.snapshot_wait() == 1
+    g.ctx.sync()
+    for dst in (dev, pinned, pageable, inside):
+        assert all(torch.equal(d.cpu(), x.cpu()) for d, x in zip(dst, (g.p, g.m, g.v)))
+    g.close()
+
+
 @pytest.mark.parametrize("clip,refold,streams,batch_bytes,optimizer", [(0.01, False, 2, 0, "adamw"), (0.0, False, 3, 1 << 20, "adamw"),
                                                                        (0.01, True, 2, 1 << 62, "adamw"), (0.01, False, 1, 0, "sgd"),
                                                                        (0.0, False, 2, 0, "adam")])
