@@ -231,7 +231,18 @@ def main() -> int:
     A = g.layout.arena_numel
     snap_dev = snap_host = None
     if snapshots and args.snapshot_host:
-        snap_host = [torch.empty(A, dtype=torch.float32, pin_memory=True) for _ in range(3)]
+        # pinned host arrays for param, m, v; where the host cannot pin that much, as many of them as it can (the rest
+        # of the snapshot then stays in the staging set / is not copied)
+        snap_host = []
+        for _ in range(3):
+            try:
+                snap_host.append(torch.empty(A, dtype=torch.float32, pin_memory=True))
+            except RuntimeError:
+                torch.cuda.synchronize()
+                break
+        if not snap_host:
+            print("bench.py: cannot pin host memory for one array of the replica", file=sys.stderr)
+            return 2
     elif snapshots and not staged:
         snap_dev = g.snap                      # a second set of arenas, placed with everything else
     snap_taken, snap_skipped = 0, 0
@@ -240,7 +251,7 @@ def main() -> int:
         """staged snapshots are armed before the iteration whose end state they hold"""
         nonlocal snap_taken, snap_skipped
         if staged and (i + 1) % args.snapshot_every == 0:
-            rc = g.ctx.try_snapshot_arm(*([h.data_ptr() for h in snap_host] if snap_host else [None, None, None]))
+            rc = g.ctx.try_snapshot_arm(*(([h.data_ptr() for h in snap_host] + [None, None])[:3] if snap_host else [None, None, None]))
             if rc == sh.binding.OK:
                 snap_taken += 1
             elif rc == sh.binding.EBUSY:
@@ -252,7 +263,7 @@ def main() -> int:
         nonlocal snap_taken
         if snapshots and not staged and (i + 1) % args.snapshot_every == 0:
             dst = snap_host if snap_host else snap_dev
-            g.ctx.snapshot(*(d.data_ptr() for d in dst))
+            g.ctx.snapshot(*([d.data_ptr() for d in dst] + [None, None])[:3])
             snap_taken += 1
 
     if ingest:
@@ -393,8 +404,9 @@ def main() -> int:
     }
     if snapshots:
         sc = kernels.get("snapshot_copies")
-        nbytes = A * 4 * (2 if args.optimizer == "sgd" else 3)
+        nbytes = A * 4 * (len(snap_host) if snap_host else (2 if args.optimizer == "sgd" else 3))
         out["snapshots"] = {"taken": snap_taken, "skipped_while_draining": snap_skipped,
+                            "host_arrays": len(snap_host) if snap_host else 0,
                             "copy_ms_each": sc["avg_ms"] if sc else None,
                             "copy_GBps": (nbytes / (sc["avg_ms"] * 1e-3) / 1e9) if sc and (args.snapshot_host or not staged) else None,
                             "ms_per_step_updates_only": 1e3 * t_updates / args.steps,
