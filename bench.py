@@ -27,14 +27,14 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 # its defaults (profiles/*_bench_rocprofv3.md), each counter scaled by what it reads for the library's plain copy
 # kernel over 1 GiB.  Keyed by (workload, kernel, --refold, --no-clip); only reported for default settings and while
 # the kernel sources still hash to the value the counters were taken at.
-MEASURED_TRAFFIC_SOURCES_SHA256 = "f915f9a7b09a55b6935f490dc0b9dc3fb3f8272805ec9ef46c0869196195b42b"
+MEASURED_TRAFFIC_SOURCES_SHA256 = "d7cbd9352a772d11be0c5e54adf2346de18d1990291fdeecbc17f29d2fac9c4c"
 MEASURED_TRAFFIC = {
-    ("llama7b", "k_adamw", False, False): 188701134326.7,
-    ("ragged7b", "k_fold_sumsq", False, False): 5669629383.3,
-    ("gpt1p3b", "k_fold_sumsq", False, False): 4744684467.9,
-    ("llama7b_w1", "k_fold_adamw", True, False): 21902630125.4,
-    ("gpt2s", "k_fold_adamw", False, False): 4978099181.8,
-    ("llama7b", "k_fold_adamw", False, True): 11231576737.6,
+    ("llama7b", "k_adamw", False, False): 188701809354.5,
+    ("ragged7b", "k_fold_sumsq", False, False): 5669635031.7,
+    ("gpt1p3b", "k_fold_sumsq", False, False): 4744672748.8,
+    ("llama7b_w1", "k_fold_adamw", True, False): 21902519508.3,
+    ("gpt2s", "k_fold_adamw", False, False): 4978133478.6,
+    ("llama7b", "k_fold_adamw", False, True): 11231851568.5,
 }
 KERNEL_SOURCES = ("paper_2507_13522_amd/csrc/shadow_kernels.hip.h", "paper_2507_13522_amd/csrc/shadow.hip")
 

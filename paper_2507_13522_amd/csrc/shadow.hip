@@ -891,20 +891,40 @@ int32_t precheck_bucket(const shadow_ctx* c, uint32_t bucket_id, const void* con
     return SHADOW_OK;
 }
 
+// The plain copy kernel over `bytes` (a multiple of 16) on `stream`, as several launches where one would be too large.
+int32_t launch_copy(void* d_dst, const void* d_src, uint64_t bytes, hipStream_t stream, uint64_t max_launch_threads)
+{
+    const uint64_t n16 = bytes >> 4;
+    const uint32_t block = 256;
+    uint64_t per_launch = max_launch_threads / block;
+    if (per_launch < 1) per_launch = 1;
+    const uint64_t blocks = (n16 + block - 1) / block;
+    for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
+        const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
+        k_copy<<<uint32_t(nb), block, 0, stream>>>(static_cast<const u32x4*>(d_src), static_cast<u32x4*>(d_dst), n16, b0);
+    }
+    HIP_TRY(hipGetLastError());
+    return SHADOW_OK;
+}
+
 // One array of the replica (or of the staging set) to a snapshot destination, on the copy stream.  Pinned host
-// memory is written by the small drain kernel through its device-side mapping; device memory (and host memory the
-// device cannot address) by the runtime's copy.
+// memory is written by the small drain kernel through its device-side mapping, device memory by the plain copy
+// kernel (twice the rate of the runtime's device-to-device copy here), host memory the device cannot address by
+// the runtime's copy.
 int32_t snapshot_copy(shadow_ctx* c, float* dst, const float* src, size_t bytes)
 {
     hipPointerAttribute_t attr{};
+    const bool known = hipPointerGetAttributes(&attr, dst) == hipSuccess;
+    if (!known) (void)hipGetLastError();          // a pointer the runtime does not know leaves an error behind: not ours
+    const bool vec = aligned(dst, 16) && bytes % 16 == 0;
     void* mapped = nullptr;
-    if (hipPointerGetAttributes(&attr, dst) == hipSuccess && attr.type == hipMemoryTypeHost &&
-        hipHostGetDevicePointer(&mapped, dst, 0) == hipSuccess && mapped && aligned(mapped, 16) && bytes % 16 == 0) {
+    if (known && vec && attr.type == hipMemoryTypeHost && hipHostGetDevicePointer(&mapped, dst, 0) == hipSuccess && mapped &&
+        aligned(mapped, 16)) {
         k_drain<<<c->drain_blocks, 256, 0, c->snap_stream>>>(reinterpret_cast<const u32x4*>(src), static_cast<u32x4*>(mapped), bytes >> 4);
         HIP_TRY(hipGetLastError());
         return SHADOW_OK;
     }
-    (void)hipGetLastError();          // a pointer the runtime does not know leaves an error behind: not ours
+    if (known && vec && attr.type == hipMemoryTypeDevice) return launch_copy(dst, src, bytes, c->snap_stream, c->max_launch_threads);
     HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, c->snap_stream));
     return SHADOW_OK;
 }
@@ -1510,19 +1530,8 @@ int32_t shadow_copy_probe(void* d_dst, const void* d_src, uint64_t bytes, void* 
 {
     if (!d_dst || !d_src || (bytes & 15) || !aligned(d_dst, 16) || !aligned(d_src, 16)) return SHADOW_EINVAL;
     if (max_launch_threads > kMaxThreadsPerLaunch) return SHADOW_EINVAL;
-    const uint64_t n16 = bytes >> 4;
-    if (n16 == 0) return SHADOW_OK;
-    const uint32_t block = 256;
-    uint64_t per_launch = (max_launch_threads ? max_launch_threads : kMaxThreadsPerLaunch) / block;
-    if (per_launch < 1) per_launch = 1;
-    const uint64_t blocks = (n16 + block - 1) / block;
-    for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
-        const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
-        k_copy<<<uint32_t(nb), block, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const u32x4*>(d_src),
-                                                                             static_cast<u32x4*>(d_dst), n16, b0);
-    }
-    HIP_TRY(hipGetLastError());
-    return SHADOW_OK;
+    if (bytes == 0) return SHADOW_OK;
+    return launch_copy(d_dst, d_src, bytes, static_cast<hipStream_t>(stream), max_launch_threads ? max_launch_threads : kMaxThreadsPerLaunch);
 }
 
 const char* shadow_strerror(int32_t status)

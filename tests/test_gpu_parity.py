@@ -287,7 +287,9 @@ def test_ingest_from_pinned_host(slots, streams, clip):
             if (b + t) % 3 == 0:
                 g.ctx.apply_bucket(b, g._views[b], t)                # device views
             else:
-                g.ctx.ingest_bucket(b, [h.data_ptr() for h in host[b]], t)
+                ready = torch.cuda.Event()
+                ready.record()              # stands for a device-side producer of the host views
+                g.ctx.ingest_bucket(b, [h.data_ptr() for h in host[b]], t, ready_event=ready.cuda_event if b % 2 else None)
         assert g.ctx.try_apply_bucket(0, g._views[0], t) == binding.ESTEP   # iteration t is complete
         g.ctx.sync()
         orc.step({b: [h.numpy().view(np.uint16) for h in host[b]] for b in range(B)})
@@ -651,6 +653,54 @@ def test_exactly_once_errors_leave_state_untouched():
     for b in range(B):
         assert_state_matches(g.bucket_state(b), (orc.p[b], orc.m[b], orc.v[b]), f"errors bucket {b}")
     g.close()
+
+
+def test_snapshot_and_event_calls_refuse_bad_arguments():
+    """Argument checks of the staged-snapshot and producer/consumer calls; nothing they refuse changes the replica."""
+    say("case snapshot/event errors")
+    wl = custom("snap-errors", [(5000, True), (6000, False), (7000, True)], 2, "bf16", clip=0.01, cap=12_000, steps=1)
+    g = GpuShadow(wl, Inputs(wl))
+    L, h = sh.lib(), g.ctx._h
+    A = g.layout.arena_numel
+    B = len(g.buckets)
+    stage = [torch.zeros(A + 64, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    sp = [t.data_ptr() for t in stage]
+    ev = torch.cuda.Event()
+    ev.record()
+    before = [x.clone() for x in (g.p, g.m, g.v)]
+    assert L.shadow_snapshot_arm(h, None, None, None) == binding.EINVAL                 # no staging set lent yet
+    assert L.shadow_snapshot_record(h, ev.cuda_event) == binding.EINVAL                 # no snapshot requested yet
+    assert L.shadow_snapshot_attach(h, sp[0], sp[1], None) == binding.EINVAL            # AdamW has a second state array
+    assert L.shadow_snapshot_attach(h, sp[0] + 4, sp[1], sp[2]) == binding.EINVAL       # misaligned
+    assert L.shadow_snapshot_attach(h, sp[0], sp[0], sp[2]) == binding.EINVAL           # the same array twice
+    assert L.shadow_snapshot_attach(h, g.p.data_ptr(), sp[1], sp[2]) == binding.EINVAL  # the replica itself
+    assert L.shadow_snapshot_attach(h, sp[0], sp[1], sp[2]) == binding.OK
+    assert L.shadow_snapshot_attach(h, sp[0], sp[1], sp[2]) == binding.EINVAL           # at most once
+    assert L.shadow_record_consumed(h, B, ev.cuda_event) == binding.EBUCKET
+    assert L.shadow_record_consumed(h, 0, None) == binding.EINVAL
+    assert L.shadow_record_consumed(h, 0, ev.cuda_event) == binding.OK                  # nothing pending: records at once
+    ev.synchronize()
+    g.fill_grads(1)
+    g.ctx.apply_bucket(0, g._views[0], 1, ready_event=ev.cuda_event)
+    assert L.shadow_snapshot_attach(h, sp[0], sp[1], sp[2]) == binding.EINVAL
+    assert L.shadow_snapshot_arm(h, None, None, None) == binding.EBUSY                  # an iteration is open
+    for b in range(1, B):
+        g.ctx.apply_bucket(b, g._views[b], 1)
+    g.ctx.sync()
+    assert all(not torch.equal(a, b) for a, b in zip(before[:1], (g.p,)))
+    assert all(float(t.abs().max()) == 0.0 for t in stage)                              # never armed: staging set untouched
+    g.close()
+    # folding twice (no scratch arena): the views are read again at the end of the iteration, no release before that
+    wl2 = custom("snap-errors-refold", [(5000, True), (6000, False), (7000, True)], 1, "bf16", clip=0.01, cap=12_000, steps=1)
+    g2 = GpuShadow(wl2, Inputs(wl2), refold=True)
+    g2.fill_grads(1)
+    g2.ctx.apply_bucket(0, g2._views[0], 1)
+    assert sh.lib().shadow_record_consumed(g2.ctx._h, 0, ev.cuda_event) == binding.EBUSY
+    for b in range(1, len(g2.buckets)):
+        g2.ctx.apply_bucket(b, g2._views[b], 1)
+    assert sh.lib().shadow_record_consumed(g2.ctx._h, 0, ev.cuda_event) == binding.OK
+    ev.synchronize()
+    g2.close()
 
 
 def test_per_step_learning_rate():
