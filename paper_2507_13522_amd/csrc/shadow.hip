@@ -36,7 +36,7 @@ constexpr uint32_t kFoldBytesInFlightPerCu = 96 * 1024;
 constexpr uint32_t kFusedBytesInFlightPerCu = 80 * 1024;
 constexpr uint64_t kFusedSmallLaunchElems = 1ull << 27;
 constexpr uint32_t kDefaultSweepBlock = 256;     // threads per block of the whole-arena optimizer sweep
-constexpr uint32_t kDefaultFoldWaves = 32;       // waves a CU may hold: no bound for the per-bucket kernels,
+constexpr uint32_t kDefaultFoldWaves = 32;       // waves a CU may hold: no bound for 1024-thread fold blocks,
 constexpr uint32_t kDefaultSweepWaves = 16;      // 4 blocks of 256 threads for the sweep
 constexpr uint32_t kDefaultDrainBlocks = 4;      // blocks of the kernel that drains a snapshot to the host
 constexpr uint32_t kLdsPerCu = 160 * 1024;
@@ -264,7 +264,6 @@ uint32_t sumsq_vpl(const shadow_hparams& hp)
     }
 }
 
-// blocks of a bucket's launch: update == false is the fold + sum-of-squares kernel
 // blocks of a bucket in the fold + sum-of-squares kernel
 uint32_t bucket_blocks(const shadow_ctx* c, uint64_t numel)
 {
@@ -313,14 +312,15 @@ struct ProfScope {
     }
 };
 
-// update == false: the fold of an arriving bucket (with clipping: sum of squares, reduced gradient stored unless
-// re-fold mode).  update == true: fold + AdamW (clipping off: the only pass; re-fold mode: the second pass, scaled
-// by the clip coefficient).
+// The staging set while the running iteration is armed for a snapshot, else nothing.
 SnapSet snap_set(const shadow_ctx* c)
 {
     return c->snap_active ? SnapSet{c->stage_p, c->stage_m, c->stage_v} : SnapSet{nullptr, nullptr, nullptr};
 }
 
+// update == false: the fold of an arriving bucket (with clipping: sum of squares, reduced gradient stored unless
+// re-fold mode).  update == true: fold + optimizer (clipping off: the only pass; re-fold mode: the second pass,
+// scaled by the clip coefficient).
 template <bool BF16, int W>
 void launch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_t st, const WdMap& map, bool update, uint32_t fused_block,
                  uint32_t fused_lds)
