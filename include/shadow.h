@@ -85,7 +85,7 @@ typedef struct {
  *                             memory (default 4, at most 4096): few on purpose.  Measured: once the stores
  *                             to the host saturate the link (8 blocks and more, and the runtime's own
  *                             device-to-host copy kernel) every kernel that runs beside them slows by
- *                             50-100 %; at 1-4 blocks (10-25 GB/s to the host) by 3-6 %.
+ *                             50-100 %; at 1-4 blocks (10-34 GB/s to the host) by 3-7 %.
  *   max_launch_threads        a logical launch with more threads is issued as several launches
  *                             (default and upper limit 2^31; lower values exist so that tests can
  *                             reach the split paths with small inputs; at least one block and one

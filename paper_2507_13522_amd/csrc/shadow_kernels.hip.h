@@ -556,7 +556,7 @@ __global__ __launch_bounds__(kMaxBlock) void k_copy(const u32x4* __restrict__ sr
 // blocks on purpose.  Measured on MI355X: while stores to the host saturate the link (this
 // kernel with 8 blocks or more, and equally the runtime's own device-to-host copy kernel), every
 // kernel that runs beside them takes 1.5 to 2 times as long, although the link carries under
-// 1 % of the HBM rate; with 1 to 4 blocks (10-25 GB/s to the host) the others lose 3-6 %.
+// 1 % of the HBM rate; with 1 to 4 blocks (10-34 GB/s to the host) the others lose 3-7 %.
 // Every lane walks the array with the grid's stride, four vectors in flight, until it is past
 // the end.
 __global__ __launch_bounds__(256) void k_drain(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n16)
