@@ -160,6 +160,7 @@ def main() -> int:
                     help="clipping without a scratch arena: fold the views twice instead of storing the reduced gradient")
     ap.add_argument("--optimizer", default="adamw", choices=["adamw", "adam", "sgd"])
     ap.add_argument("--no-clip", action="store_true", help="run the workload without global-norm clipping (fused kernel)")
+    ap.add_argument("--workers", type=int, default=0, help="override the workload's number of workers W")
     ap.add_argument("--ingest-slots", type=int, default=0,
                     help="hand the buckets over as pinned HOST views through a device ring of this many slots "
                          "(PCIe-inclusive rate; never the headline value)")
@@ -205,7 +206,7 @@ def main() -> int:
 
     default_settings = (args.streams is None and args.batch_mib is None and args.optimizer == "adamw" and not args.ingest_slots
                         and not args.fold_block and not args.fused_block and not args.sweep_block and not args.fold_waves and not args.fused_waves and not args.sweep_waves
-                        and args.placement == "auto" and not args.offsets_gib and not args.snapshot_every and not args.view_ring_gib)
+                        and args.placement == "auto" and not args.workers and not args.offsets_gib and not args.snapshot_every and not args.view_ring_gib)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -216,6 +217,8 @@ def main() -> int:
     wl = synth.get_workload(args.workload)
     if args.no_clip:
         wl.max_grad_norm = 0.0
+    if args.workers:
+        wl.num_workers = args.workers
     inputs = Inputs(wl, period=TILE_PERIOD)
     ingest = args.ingest_slots > 0
     # all W views of every bucket resident when they fit beside the replica; otherwise (W = 32 at 7B: 445 GB) the

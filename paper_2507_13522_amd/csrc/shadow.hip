@@ -260,9 +260,15 @@ uint32_t sumsq_vpl(const shadow_hparams& hp)
         case 8: return bf16 ? fold_vpl<true, 8>() : fold_vpl<false, 8>();
         case 16: return bf16 ? fold_vpl<true, 16>() : fold_vpl<false, 16>();
         case 32: return bf16 ? fold_vpl<true, 32>() : fold_vpl<false, 32>();
+        case 64: return bf16 ? fold_vpl<true, 64>() : fold_vpl<false, 64>();
         default: return 1;      // run-time worker count
     }
 }
+
+// Worker counts the kernels are instantiated for: all loads of a lane are then issued before the first add.  Any
+// other count takes the run-time loop, whose loads follow each other; it wants all the waves it can get.
+bool unrolled_workers(uint32_t w) { return w == 1 || w == 2 || w == 4 || w == 8 || w == 16 || w == 32 || w == 64; }
+constexpr uint32_t kLoopBlock = 128;     // measured on W = 3, 6, 24, 64: 128-thread blocks, 32 waves, both per-bucket kernels
 
 // blocks of a bucket in the fold + sum-of-squares kernel
 uint32_t bucket_blocks(const shadow_ctx* c, uint64_t numel)
@@ -273,8 +279,10 @@ uint32_t bucket_blocks(const shadow_ctx* c, uint64_t numel)
 // Launch shape of the fold + optimizer kernel for a launch list of total_elems elements.
 void fused_shape(const shadow_ctx* c, uint64_t total_elems, uint32_t* block, uint32_t* lds)
 {
-    *block = c->fused_block_given ? c->fused_block_given : (total_elems < kFusedSmallLaunchElems ? 64u : 128u);
+    const bool unrolled = unrolled_workers(c->hp.num_workers);
+    *block = c->fused_block_given ? c->fused_block_given : (!unrolled ? kLoopBlock : total_elems < kFusedSmallLaunchElems ? 64u : 128u);
     uint32_t waves = c->fused_waves;
+    if (!waves && !unrolled) waves = 32;
     if (!waves) {
         const uint32_t state_bytes = c->hp.optimizer == SHADOW_OPT_SGD ? 32u : 48u;
         const uint32_t lane_bytes = kVec * c->lay.grad_elem_bytes * c->hp.num_workers + state_bytes;
@@ -348,6 +356,7 @@ void dispatch_fold(shadow_ctx* c, const FoldBatch& fb, uint32_t grid, hipStream_
         case 8: launch_fold<BF16, 8>(c, fb, grid, st, map, update, fblock, flds); break;
         case 16: launch_fold<BF16, 16>(c, fb, grid, st, map, update, fblock, flds); break;
         case 32: launch_fold<BF16, 32>(c, fb, grid, st, map, update, fblock, flds); break;
+        case 64: launch_fold<BF16, 64>(c, fb, grid, st, map, update, fblock, flds); break;
         default: launch_fold<BF16, 0>(c, fb, grid, st, map, update, fblock, flds);
     }
 }
@@ -783,8 +792,9 @@ int32_t check_replica_args(const shadow_layout* layout, const shadow_hparams* hp
 void set_launch_shape(shadow_ctx* c, const shadow_launch_shape& ls)
 {
     const uint32_t fold_lane_bytes = kVec * c->lay.grad_elem_bytes * c->hp.num_workers * sumsq_vpl(c->hp);
-    const bool wide = fold_lane_bytes > 64;
-    c->fold_block = ls.fold_block ? ls.fold_block : (wide ? kWideFoldBlock : kDefaultFoldBlock);
+    const bool unrolled = unrolled_workers(c->hp.num_workers);
+    const bool wide = unrolled && fold_lane_bytes > 64;
+    c->fold_block = ls.fold_block ? ls.fold_block : (!unrolled ? kLoopBlock : wide ? kWideFoldBlock : kDefaultFoldBlock);
     uint32_t fold_waves = ls.fold_waves_per_cu;
     if (!fold_waves) {
         fold_waves = kDefaultFoldWaves;
