@@ -161,6 +161,7 @@ def main() -> int:
     ap.add_argument("--optimizer", default="adamw", choices=["adamw", "adam", "sgd"])
     ap.add_argument("--no-clip", action="store_true", help="run the workload without global-norm clipping (fused kernel)")
     ap.add_argument("--workers", type=int, default=0, help="override the workload's number of workers W")
+    ap.add_argument("--grad-dtype", default=None, choices=["bf16", "f32"], help="override the workload's gradient type")
     ap.add_argument("--ingest-slots", type=int, default=0,
                     help="hand the buckets over as pinned HOST views through a device ring of this many slots "
                          "(PCIe-inclusive rate; never the headline value)")
@@ -206,7 +207,7 @@ def main() -> int:
 
     default_settings = (args.streams is None and args.batch_mib is None and args.optimizer == "adamw" and not args.ingest_slots
                         and not args.fold_block and not args.fused_block and not args.sweep_block and not args.fold_waves and not args.fused_waves and not args.sweep_waves
-                        and args.placement == "auto" and not args.workers and not args.offsets_gib and not args.snapshot_every and not args.view_ring_gib)
+                        and args.placement == "auto" and not args.workers and not args.grad_dtype and not args.offsets_gib and not args.snapshot_every and not args.view_ring_gib)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -219,6 +220,8 @@ def main() -> int:
         wl.max_grad_norm = 0.0
     if args.workers:
         wl.num_workers = args.workers
+    if args.grad_dtype:
+        wl.grad_dtype = args.grad_dtype
     inputs = Inputs(wl, period=TILE_PERIOD)
     ingest = args.ingest_slots > 0
     # all W views of every bucket resident when they fit beside the replica; otherwise (W = 32 at 7B: 445 GB) the

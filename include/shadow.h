@@ -71,7 +71,7 @@ typedef struct {
 /* Launch shape of the kernels of ONE replica (part of shadow_hparams; every field 0 = the
  * library's default, which is what was measured fastest on MI355X).  Results never depend on it.
  *   fold_block, fused_block, sweep_block   threads per block of the per-bucket fold + sum-of-squares
- *                             kernel (default: 1024 while a lane loads at most 64 bytes of views, else 128),
+ *                             kernel (default: 1024 when a lane's 4 elements are exactly 64 bytes of views, else 128),
  *                             of the per-bucket fold + optimizer kernel (default: 64 for launches under 2^27
  *                             elements, else 128) and of the whole-arena optimizer sweep (default 256):
  *                             64, 128, 256, 512 or 1024.

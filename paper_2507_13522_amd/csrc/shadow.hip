@@ -22,10 +22,11 @@ namespace {
 thread_local std::string g_hip_error;
 
 constexpr uint64_t kMaxThreadsPerLaunch = 1ull << 31;
-// The fold + sum-of-squares kernel streams W arrays in and one out.  While a lane loads at most 64 bytes (W <= 8 bf16
-// views, or several narrow groups) 1024-thread blocks without a bound on the waves are fastest; with more bytes per
-// lane (W = 16, 32) 128-thread blocks and about 96 KiB of loads in flight per CU, but at least 8 waves (measured:
-// W = 16: 12 waves, -5 % time; W = 32: 8 waves, -4 %; fewer than 8 waves: +15 %).
+// The fold + sum-of-squares kernel streams W arrays in and one out.  Measured: when a lane's one group of 4 elements
+// is exactly 64 bytes of views (W = 8 bf16, W = 4 float) 1024-thread blocks without a bound on the waves are fastest;
+// when the lane owns several narrow groups (W = 1, 2, 4 bf16; W = 1, 2 float) 128-thread blocks without a bound
+// (-3 ... -10 % time); with more bytes per lane (W = 16, 32, 64) 128-thread blocks and about 96 KiB of loads in flight
+// per CU, but at least 8 waves (W = 16: 12 waves, -5 %; W = 32: 8 waves, -4 %; fewer than 8 waves: +15 %).
 constexpr uint32_t kDefaultFoldBlock = 1024;
 constexpr uint32_t kWideFoldBlock = 128;
 constexpr uint32_t kFoldBytesInFlightPerCu = 96 * 1024;
@@ -794,7 +795,8 @@ void set_launch_shape(shadow_ctx* c, const shadow_launch_shape& ls)
     const uint32_t fold_lane_bytes = kVec * c->lay.grad_elem_bytes * c->hp.num_workers * sumsq_vpl(c->hp);
     const bool unrolled = unrolled_workers(c->hp.num_workers);
     const bool wide = unrolled && fold_lane_bytes > 64;
-    c->fold_block = ls.fold_block ? ls.fold_block : (!unrolled ? kLoopBlock : wide ? kWideFoldBlock : kDefaultFoldBlock);
+    const bool narrow = unrolled && sumsq_vpl(c->hp) > 1;
+    c->fold_block = ls.fold_block ? ls.fold_block : (!unrolled ? kLoopBlock : (wide || narrow) ? kWideFoldBlock : kDefaultFoldBlock);
     uint32_t fold_waves = ls.fold_waves_per_cu;
     if (!fold_waves) {
         fold_waves = kDefaultFoldWaves;
