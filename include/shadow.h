@@ -81,8 +81,9 @@ typedef struct {
  *                             unit; about 80 KiB for the fold + optimizer kernel; never fewer than 8 waves;
  *                             16 for the sweep.  Fewer requests in flight keep DRAM rows open longer; enforced
  *                             by reserving unused LDS, in whole blocks and at most 64 KiB per block.  Worker
- *                             counts other than 1, 2, 4, 8, 16, 32, 64 run a loop over the workers instead of
- *                             unrolled loads: their per-bucket kernels default to 128-thread blocks, no bound.
+ *                             counts other than 1, 2, 4, 8, 16, 32, 64 run a loop that takes the views 8 at a
+ *                             time instead of fully unrolled loads: their per-bucket kernels default to
+ *                             128-thread blocks, no bound.
  *   drain_blocks              256-thread blocks of the kernel that writes a snapshot to pinned host
  *                             memory (default 4, at most 4096): few on purpose.  Measured: once the stores
  *                             to the host saturate the link (8 blocks and more, and the runtime's own

@@ -267,9 +267,9 @@ uint32_t sumsq_vpl(const shadow_hparams& hp)
 }
 
 // Worker counts the kernels are instantiated for: all loads of a lane are then issued before the first add.  Any
-// other count takes the run-time loop, whose loads follow each other; it wants all the waves it can get.
+// other count takes the run-time loop, 8 views at a time; its registers do not grow with W, so it runs unbounded.
 bool unrolled_workers(uint32_t w) { return w == 1 || w == 2 || w == 4 || w == 8 || w == 16 || w == 32 || w == 64; }
-constexpr uint32_t kLoopBlock = 128;     // measured on W = 3, 6, 24, 64: 128-thread blocks, 32 waves, both per-bucket kernels
+constexpr uint32_t kLoopBlock = 128;     // measured on W = 3, 6, 24: 128-thread blocks, 32 waves, both per-bucket kernels
 
 // blocks of a bucket in the fold + sum-of-squares kernel
 uint32_t bucket_blocks(const shadow_ctx* c, uint64_t numel)

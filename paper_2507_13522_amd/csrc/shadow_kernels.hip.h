@@ -192,6 +192,44 @@ __device__ __forceinline__ f32x4 reduce_views4(const typename RawVec<BF16>::type
     return r;
 }
 
+// Worker count known only at run time: the views are taken in chunks of kLoopChunk, every load of a chunk issued
+// before its adds, the adds still strictly in worker order.
+constexpr int kLoopChunk = 8;
+template <bool BF16>
+__device__ __forceinline__ void accumulate_view(const typename RawVec<BF16>::type& a, bool first, f32x4& r)
+{
+    if constexpr (BF16) {
+        if (first) widen_first(a, r); else widen_add(a, r);
+    } else {
+        if (first) r = a; else r = r + a;
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ f32x4 fold4_loop(const void* const* vp, uint32_t w_rt, uint64_t vec)
+{
+    typedef typename RawVec<BF16>::type V;
+    f32x4 r = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint32_t w0 = 0;
+    for (; w0 + kLoopChunk <= w_rt; w0 += kLoopChunk) {
+        V raw[kLoopChunk];
+#pragma unroll
+        for (int j = 0; j < kLoopChunk; ++j) raw[j] = load_once(reinterpret_cast<const V*>(vp[w0 + j]) + vec);
+#pragma unroll
+        for (int j = 0; j < kLoopChunk; ++j) accumulate_view<BF16>(raw[j], j == 0 && w0 == 0, r);
+    }
+    if (w0 < w_rt) {
+        V raw[kLoopChunk];
+#pragma unroll
+        for (int j = 0; j < kLoopChunk - 1; ++j)
+            if (w0 + j < w_rt) raw[j] = load_once(reinterpret_cast<const V*>(vp[w0 + j]) + vec);
+#pragma unroll
+        for (int j = 0; j < kLoopChunk - 1; ++j)
+            if (w0 + j < w_rt) accumulate_view<BF16>(raw[j], j == 0 && w0 == 0, r);
+    }
+    return r;
+}
+
 template <bool BF16, int W>
 __device__ __forceinline__ f32x4 fold4(const void* const* vp, uint32_t w_rt, uint64_t vec, const StepScalars& s)
 {
@@ -202,8 +240,7 @@ __device__ __forceinline__ f32x4 fold4(const void* const* vp, uint32_t w_rt, uin
             load_views4<true, W>(vp, vec, raw);
             return reduce_views4<true, W>(raw, s);
         } else {
-            widen_first(load_once(reinterpret_cast<const u32x2*>(vp[0]) + vec), r);
-            for (uint32_t w = 1; w < w_rt; ++w) widen_add(load_once(reinterpret_cast<const u32x2*>(vp[w]) + vec), r);
+            r = fold4_loop<true>(vp, w_rt, vec);
         }
     } else {
         if constexpr (W > 0) {
@@ -222,8 +259,7 @@ __device__ __forceinline__ f32x4 fold4(const void* const* vp, uint32_t w_rt, uin
                 }
             }
         } else {
-            r = load_once(reinterpret_cast<const f32x4*>(vp[0]) + vec);
-            for (uint32_t w = 1; w < w_rt; ++w) r = r + load_once(reinterpret_cast<const f32x4*>(vp[w]) + vec);
+            r = fold4_loop<false>(vp, w_rt, vec);
         }
     }
     if (s.mean) r = r * s.inv_w;
