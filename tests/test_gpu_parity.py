@@ -91,7 +91,8 @@ def test_many_small_buckets_batched(W, dtype, clip):
         check_against_oracle(wl, num_streams=streams, batch_bytes=bb)
 
 
-@pytest.mark.parametrize("W", [1, 2, 4, 6, 8, 16, 32, 64])
+# 3, 6, 7: only the remainder of the worker loop; 9, 15, 17: whole chunks of 8 and a remainder; 24, 40: whole chunks only
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 6, 7, 8, 9, 15, 16, 17, 24, 32, 40, 64])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("clip", [0.0, 0.005])
 def test_worker_counts(W, dtype, clip):
