@@ -1144,17 +1144,18 @@ int32_t shadow_ingest_attach(shadow_ctx* c, void* d_ring, uint64_t ring_bytes)
     const uint64_t nslots = ring_bytes / slot_bytes;
     if (nslots < 1) return SHADOW_EINVAL;
     const uint32_t n = uint32_t(nslots > 64 ? 64 : nslots);
-    HIP_TRY(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+    // a call that failed half-way left its stream and events with the context: they are used again, not made twice
+    if (!c->copy_stream) HIP_TRY(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
     try {
-        c->copied_ev.assign(n, nullptr);
-        c->consumed_ev.assign(n, nullptr);
+        if (c->copied_ev.size() < n) c->copied_ev.resize(n, nullptr);
+        if (c->consumed_ev.size() < n) c->consumed_ev.resize(n, nullptr);
         c->consumed_valid.assign(n, 0);
     } catch (const std::bad_alloc&) {
         return SHADOW_ENOMEM;
     }
     for (uint32_t i = 0; i < n; ++i) {
-        HIP_TRY(hipEventCreateWithFlags(&c->copied_ev[i], hipEventDisableTiming));
-        HIP_TRY(hipEventCreateWithFlags(&c->consumed_ev[i], hipEventDisableTiming));
+        if (!c->copied_ev[i]) HIP_TRY(hipEventCreateWithFlags(&c->copied_ev[i], hipEventDisableTiming));
+        if (!c->consumed_ev[i]) HIP_TRY(hipEventCreateWithFlags(&c->consumed_ev[i], hipEventDisableTiming));
     }
     c->ring = static_cast<char*>(d_ring);
     c->view_stride = view_stride;

@@ -384,15 +384,13 @@ __global__ __launch_bounds__(kMaxBlock) void k_fold_adamw(FoldBatch fb, float* _
 // launched (W = 1 bf16: 8 bytes), so the lane owns kVpl groups of 4 elements, blockDim apart
 // (every load instruction of a wave still covers one contiguous run), chosen so that a lane
 // reads at least 64 bytes.
-#ifndef SHADOW_FOLD_LANE_BYTES
-#define SHADOW_FOLD_LANE_BYTES 64
-#endif
+constexpr int kFoldLaneBytes = 64;
 template <bool BF16, int W>
 constexpr int fold_vpl()
 {
     if (W <= 0) return 1;
     const int bytes = 4 * (BF16 ? 2 : 4) * (W > 0 ? W : 1);
-    const int v = SHADOW_FOLD_LANE_BYTES / bytes;
+    const int v = kFoldLaneBytes / bytes;
     return v < 1 ? 1 : (v > 8 ? 8 : v);
 }
 
