@@ -55,7 +55,7 @@ def pick_buckets(lay: oracle.Layout, budget: int):
 
 
 def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resident: bool, num_streams: int = 2,
-                 batch_bytes: int = 0, refold: bool = False, also_sizes=()):
+                 batch_bytes: int = 0, refold: bool = False, also_sizes=(), staged_last: bool = False):
     wl = synth.get_workload(name)
     say(f"case fullsize {name}: P={wl.num_params} W={wl.num_workers} steps={steps}")
     t_start = time.time()
@@ -69,7 +69,8 @@ def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resi
     clip = wl.max_grad_norm > 0
     W = wl.num_workers
 
-    g = GpuShadow(wl, inp, num_streams=num_streams, resident_grads=resident, batch_bytes=batch_bytes, refold=refold)
+    g = GpuShadow(wl, inp, num_streams=num_streams, resident_grads=resident, batch_bytes=batch_bytes, refold=refold,
+                  snapshot_set=staged_last)
     B = len(g.buckets)
     ring = None
     if not resident:
@@ -116,6 +117,10 @@ def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resi
         order_t = synth.arrival_order(wl.seed, t, B) if wl.random_arrival else list(range(B))
         if resident:
             g.fill_grads(t)
+            if staged_last and t == steps:
+                for off, n, _ in g.buckets:        # whatever the staging set held, the armed iteration must overwrite it
+                    g.snap[0][off:off + n].fill_(7.0)
+                g.ctx.snapshot_arm(None, None, None)
             g.apply_step(t, order_t)
         else:
             for b in order_t:
@@ -152,6 +157,18 @@ def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resi
                 assert_state_matches(g.bucket_state(b), (orc.p[b], orc.m[b], orc.v[b]), f"{name} step {t} bucket {b}")
             got = tuple(x[s_arena_t].cpu().numpy() for x in (g.p, g.m, g.v))
             assert_state_matches(got, (sp, sm, sv), f"{name} step {t} scattered sample")
+            if staged_last and t == steps:
+                # the staging set of the armed (last) iteration: same bits as the oracle where it was recomputed,
+                # and equal to the replica everywhere
+                assert g.ctx.snapshot_wait() == steps
+                for b in chosen:
+                    off, n, _ = g.buckets[b]
+                    assert_state_matches(tuple(x[off:off + n].cpu().numpy() for x in g.snap), (orc.p[b], orc.m[b], orc.v[b]),
+                                         f"{name} step {t} bucket {b} of the staging set")
+                assert_state_matches(tuple(x[s_arena_t].cpu().numpy() for x in g.snap), (sp, sm, sv),
+                                     f"{name} step {t} scattered sample of the staging set")
+                for mine, theirs in zip(g.snap, (g.p, g.m, g.v)):
+                    assert torch.equal(mine.view(torch.int32), theirs.view(torch.int32))
         say(f"  step {t} ok" + (f" (c={float(c):.6g})" if clip else "") + f"  [{time.time() - t_start:.0f} s]")
     assert g.ctx.step() == (steps, 0)
     # alignment gaps stay zero
@@ -167,7 +184,8 @@ def test_gpt2_small_full():
 
 
 def test_gpt_1p3b_full():
-    run_fullsize("gpt1p3b", steps=10, bucket_budget=30_000_000, n_scatter=5_000_000, resident=True)
+    """The last iteration is armed for a staged snapshot: its update kernels write a second set of arenas as well."""
+    run_fullsize("gpt1p3b", steps=10, bucket_budget=30_000_000, n_scatter=5_000_000, resident=True, staged_last=True)
 
 
 def test_llama7b_full():
