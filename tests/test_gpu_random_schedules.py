@@ -19,7 +19,7 @@ def draw_case(seed: int):
     rng = np.random.default_rng(1000 + seed)
     T = int(rng.integers(3, 40))
     sizes = [(int(np.exp(rng.uniform(0, np.log(300_000)))), bool(rng.integers(0, 2))) for _ in range(T)]
-    W = int(rng.choice([1, 2, 3, 4, 8, 16]))
+    W = int(rng.choice([1, 2, 3, 4, 6, 8, 9, 16, 24]))
     dtype = str(rng.choice(["bf16", "f32"]))
     optimizer = str(rng.choice(["adamw", "adamw", "adam", "sgd"]))
     clip = float(rng.choice([0.0, 0.003, 1e6]))
@@ -37,7 +37,7 @@ def draw_case(seed: int):
     return wl, cfg, rng
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(24))
 def test_random_schedule(seed):
     wl, cfg, rng = draw_case(seed)
     print("case random schedule", seed, len(wl.tensors), "tensors W", wl.num_workers, wl.grad_dtype, "clip", wl.max_grad_norm, cfg["optimizer"],
