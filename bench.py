@@ -146,6 +146,69 @@ def cpu_baseline(wl, inputs, target_seconds: float = 15.0, optimizer: str = "ada
             "sample_single_thread": f"same buckets, {iters1} iterations, {t_used1:.1f} s on one thread"}
 
 
+PROBE_SHAPES = ((64, 12), (128, 8), (128, 16), (256, 16), (256, 0), (1024, 0))     # (threads per block, waves per CU; 0 = no bound)
+
+
+def stream_probe(torch, sh, reps: int, gib: int) -> int:
+    """What the chip sustains for the update kernels' mixes of streams: the same access pattern (one 16-byte vector per
+    lane and array, all loads first, non-temporal), launch shape and placement in HBM, without the arithmetic."""
+    GiB = 1 << 30
+    n = gib * GiB                                             # bytes per array
+    try:
+        block = torch.empty(256 * GiB, dtype=torch.uint8, device="cuda:0")
+        a = n + GiB
+        assert 3 * a <= 96 * GiB and 97 * GiB + a + 16 * (n + (2 << 20) + 4096) <= 256 * GiB, "arrays too large for the block"
+        off = {"r": 96 * GiB - 3 * a, "p": 96 * GiB - 2 * a, "m": 96 * GiB - a, "v": 97 * GiB}
+        for k in range(16):
+            off[f"g{k}"] = 97 * GiB + a + k * (n + (2 << 20) + 4096)
+        placement = "state arrays end the first 96 GiB of a 256 GiB block and start the second, views behind them"
+    except torch.OutOfMemoryError:
+        torch.cuda.empty_cache()
+        names = ["r", "p", "m", "v"] + [f"g{k}" for k in range(16)]
+        block = torch.empty(len(names) * (n + (2 << 20) + 4096), dtype=torch.uint8, device="cuda:0")
+        off = {name: i * (n + (2 << 20) + 4096) for i, name in enumerate(names)}
+        placement = "one allocation, arrays back to back"
+    for name, o in off.items():
+        block[o:o + n].zero_()
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
+    ptr = lambda name: block.data_ptr() + off[name]
+    views = lambda k: [f"g{i}" for i in range(k)]
+    mixes = [  # name, sources, destinations, block, waves per CU (the update kernel's own default shape)
+        ("copy", ["p"], ["v"], 256, 0),
+        ("reads alone, 4 arrays", ["r", "p", "m", "v"], [], 256, 16),
+        ("writes alone, 3 arrays", [], ["p", "m", "v"], 256, 16),
+        ("k_adamw: r, p, m, v in; p, m, v out in place", ["r", "p", "m", "v"], ["p", "m", "v"], 256, 16),
+        ("k_fold_sumsq W=8 bf16: 16 B/param in, r out", views(4), ["r"], 1024, 0),
+        ("k_fold_sumsq W=16 bf16: 32 B/param in, r out", views(8), ["r"], 128, 12),
+        ("k_fold_sumsq W=32 bf16: 64 B/param in, r out", views(16), ["r"], 128, 8),
+        ("k_fold_adamw W=8 bf16: 16 B/param of views, p, m, v in; p, m, v out in place", views(4) + ["p", "m", "v"], ["p", "m", "v"], 64, 11),
+    ]
+    def timed(src, dst, blk, waves):
+        call = lambda: sh.shadow_stream_probe([ptr(d) for d in dst], [ptr(x) for x in src], n, sink=sink.data_ptr(), block=blk,
+                                              waves_per_cu=waves)
+        assert call() == 0
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        return ms, (len(src) + len(dst)) * n / (ms * 1e-3) / 1e9
+
+    rows = []
+    for name, src, dst, blk, waves in mixes:
+        ms, gbps = timed(src, dst, blk, waves)
+        best = max(((timed(src, dst, b, w)[1], b, w) for b, w in PROBE_SHAPES), key=lambda t: t[0])
+        rows.append({"mix": name, "arrays_in": len(src), "arrays_out": len(dst), "block": blk, "waves_per_cu": waves or 32,
+                     "ms": ms, "GBps": gbps, "frac_of_peak": gbps / HBM_PEAK_GBS,
+                     "best_of_shapes": {"GBps": best[0], "block": best[1], "waves_per_cu": best[2] or 32}})
+    print(json.dumps({"stream_probe": rows, "bytes_per_array": n, "launches_timed": reps, "placement": placement, "peak_GBps": HBM_PEAK_GBS,
+                      "shapes_tried": [[b, w or 32] for b, w in PROBE_SHAPES]}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -191,6 +254,10 @@ def main() -> int:
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch the library's plain copy kernel once over this many MiB (known-traffic "
                          "yardstick for rocprofv3 byte counters)")
+    ap.add_argument("--stream-probe", action="store_true",
+                    help="instead of the update: time the library's streaming kernel (no arithmetic) for the mixes of read "
+                         "and written arrays that the update kernels have, and print one JSON line")
+    ap.add_argument("--probe-gib", type=int, default=4, help="GiB per array of --stream-probe (at most 8)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the shadow update runs on ONE GPU (no sharding across GPUs, no collectives); run with --gpus 1",
@@ -212,6 +279,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.stream_probe:
+        return stream_probe(torch, sh, args.steps, args.probe_gib)
     launch = sh.LaunchShape(fold_block=args.fold_block, fused_block=args.fused_block, sweep_block=args.sweep_block, fold_waves_per_cu=args.fold_waves,
                             fused_waves_per_cu=args.fused_waves, sweep_waves_per_cu=args.sweep_waves, drain_blocks=args.drain_blocks)
 

@@ -29,6 +29,23 @@ int32_t shadow_profile_read(shadow_ctx* ctx, uint32_t kind, uint64_t* launches, 
  * max_launch_threads: 0 = one launch per 2^31 threads, else as in shadow_launch_shape. */
 int32_t shadow_copy_probe(void* d_dst, const void* d_src, uint64_t bytes, void* stream, uint64_t max_launch_threads);
 
+/* A kernel that does nothing but stream: n_src device arrays in, n_dst device arrays out, `bytes`
+ * (multiple of 16) each, non-temporal 16-byte accesses, one vector per lane and array, every load of
+ * a lane issued before its first use -- the access pattern of the update kernels without their
+ * arithmetic.  It shows what the chip sustains for a given mix of read and written streams, the
+ * ceiling the update kernels are measured against.
+ *   n_src in {0, 1, 2, 4, 7, 8, 16}, n_dst in {0, 1, 3}, not both zero; other mixes: SHADOW_EINVAL.
+ *   Vector i of destination d becomes the XOR of vector i of all sources with d added to its first
+ *   32-bit word (n_src == 0: the words {i mod 2^32, 0, 0, 0} likewise).
+ *   n_dst == 0 (reads alone): d_sink names 16 writable device bytes, written only if the four words
+ *   of some XOR all equal 0x9E3779B9; otherwise d_sink may be NULL.
+ *   block: threads per block (0 = 256); waves_per_cu: bound on the waves a compute unit holds
+ *   (0 = none), both as in shadow_launch_shape.  Arrays are the caller's and 16-byte aligned.  A
+ *   destination may be one of the sources (an update in place: each lane writes the vectors it has
+ *   read); arrays must not overlap in any other way.  Enqueues on `stream` (NULL = default) and returns. */
+int32_t shadow_stream_probe(void* const* d_dst, uint32_t n_dst, const void* const* d_src, uint32_t n_src, void* d_sink, uint64_t bytes,
+                            void* stream, uint32_t block, uint32_t waves_per_cu);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,5 +27,6 @@ from .binding import (  # noqa: F401
     lib,
     shadow_apply_iteration_static,
     shadow_copy_probe,
+    shadow_stream_probe,
     shadow_strerror,
 )

@@ -92,6 +92,8 @@ _SIGS = {
     "shadow_profile_enable": [C.c_void_p, C.c_int32],
     "shadow_profile_read": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_double)],
     "shadow_copy_probe": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64],
+    "shadow_stream_probe": [C.POINTER(C.c_void_p), C.c_uint32, C.POINTER(C.c_void_p), C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p,
+                            C.c_uint32, C.c_uint32],
 }
 EXPORTS = sorted(list(_SIGS) + ["shadow_strerror", "shadow_last_hip_error", "shadow_build_id"])
 
@@ -133,6 +135,14 @@ def _check(status: int, where: str) -> None:
 
 def shadow_copy_probe(dst: int, src: int, nbytes: int, stream: int = 0, max_launch_threads: int = 0) -> None:
     _check(lib().shadow_copy_probe(dst, src, nbytes, stream, max_launch_threads), "shadow_copy_probe")
+
+
+def shadow_stream_probe(dst: Sequence[int], src: Sequence[int], nbytes: int, sink: Optional[int] = None, stream: int = 0, block: int = 0,
+                        waves_per_cu: int = 0) -> int:
+    """Status of shadow_stream_probe (OK, or EINVAL for a mix of streams the kernel is not built for)."""
+    d = (C.c_void_p * max(len(dst), 1))(*dst)
+    s = (C.c_void_p * max(len(src), 1))(*src)
+    return int(lib().shadow_stream_probe(d, len(dst), s, len(src), sink, nbytes, stream, block, waves_per_cu))
 
 
 class Layout:

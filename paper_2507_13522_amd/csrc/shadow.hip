@@ -1547,6 +1547,73 @@ int32_t shadow_copy_probe(void* d_dst, const void* d_src, uint64_t bytes, void* 
     return launch_copy(d_dst, d_src, bytes, static_cast<hipStream_t>(stream), max_launch_threads ? max_launch_threads : kMaxThreadsPerLaunch);
 }
 
+}  // extern "C"
+
+namespace {
+
+template <int R, int D>
+void launch_streams(const ProbeSet& ps, u32x4* sink, uint64_t n16, uint32_t block, uint32_t lds, hipStream_t st)
+{
+    const uint64_t per_launch = kMaxThreadsPerLaunch / block;
+    const uint64_t blocks = (n16 + block - 1) / block;
+    for (uint64_t b0 = 0; b0 < blocks; b0 += per_launch) {
+        const uint64_t nb = blocks - b0 < per_launch ? blocks - b0 : per_launch;
+        k_streams<R, D><<<uint32_t(nb), block, lds, st>>>(ps, sink, n16, b0);
+    }
+}
+
+template <int R>
+bool dispatch_streams_dst(uint32_t d, const ProbeSet& ps, u32x4* sink, uint64_t n16, uint32_t block, uint32_t lds, hipStream_t st)
+{
+    switch (d) {
+        case 0: launch_streams<R, 0>(ps, sink, n16, block, lds, st); return true;
+        case 1: launch_streams<R, 1>(ps, sink, n16, block, lds, st); return true;
+        case 3: launch_streams<R, 3>(ps, sink, n16, block, lds, st); return true;
+        default: return false;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t shadow_stream_probe(void* const* d_dst, uint32_t n_dst, const void* const* d_src, uint32_t n_src, void* d_sink, uint64_t bytes,
+                            void* stream, uint32_t block, uint32_t waves_per_cu)
+{
+    if (n_src > uint32_t(kProbeMaxSrc) || n_dst > uint32_t(kProbeMaxDst) || (n_src == 0 && n_dst == 0) || (bytes & 15)) return SHADOW_EINVAL;
+    if ((n_src && !d_src) || (n_dst && !d_dst) || (n_dst == 0 && (!d_sink || !aligned(d_sink, 16)))) return SHADOW_EINVAL;
+    if (block == 0) block = 256;
+    if (!valid_block(block) || waves_per_cu > 32) return SHADOW_EINVAL;
+    ProbeSet ps{};
+    for (uint32_t k = 0; k < n_src; ++k) {
+        if (!d_src[k] || !aligned(d_src[k], 16)) return SHADOW_EINVAL;
+        ps.src[k] = static_cast<const u32x4*>(d_src[k]);
+    }
+    for (uint32_t k = 0; k < n_dst; ++k) {
+        if (!d_dst[k] || !aligned(d_dst[k], 16)) return SHADOW_EINVAL;
+        ps.dst[k] = static_cast<u32x4*>(d_dst[k]);
+    }
+    if (bytes == 0) return SHADOW_OK;
+    const uint64_t n16 = bytes >> 4;
+    const uint32_t lds = lds_for_wave_cap(block, waves_per_cu ? waves_per_cu : 32);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    u32x4* sink = static_cast<u32x4*>(d_sink);
+    bool known = false;
+    switch (n_src) {
+        case 0: known = dispatch_streams_dst<0>(n_dst, ps, sink, n16, block, lds, st); break;
+        case 1: known = dispatch_streams_dst<1>(n_dst, ps, sink, n16, block, lds, st); break;
+        case 2: known = dispatch_streams_dst<2>(n_dst, ps, sink, n16, block, lds, st); break;
+        case 4: known = dispatch_streams_dst<4>(n_dst, ps, sink, n16, block, lds, st); break;
+        case 7: known = dispatch_streams_dst<7>(n_dst, ps, sink, n16, block, lds, st); break;
+        case 8: known = dispatch_streams_dst<8>(n_dst, ps, sink, n16, block, lds, st); break;
+        case 16: known = dispatch_streams_dst<16>(n_dst, ps, sink, n16, block, lds, st); break;
+        default: break;
+    }
+    if (!known) return SHADOW_EINVAL;          // a mix the kernel is not instantiated for
+    HIP_TRY(hipGetLastError());
+    return SHADOW_OK;
+}
+
 const char* shadow_strerror(int32_t status)
 {
     switch (status) {

@@ -585,6 +585,44 @@ __global__ __launch_bounds__(kMaxBlock) void k_copy(const u32x4* __restrict__ sr
     if (i < n16) store_once(dst + i, load_once(src + i));
 }
 
+// ---- kernel: R arrays in, D arrays out (bandwidth yardstick for a mix of streams) ----------
+// Vector i of every destination d receives the XOR of vector i of all sources, with d added to
+// its first word (R == 0: the vector {i, 0, 0, d}).  All loads of a lane are issued before the
+// first use, as in the update kernels.  D == 0 measures reads alone: the XOR is stored to
+// sink[0] only by a lane whose four words all equal kProbeNever.
+constexpr int kProbeMaxSrc = 16, kProbeMaxDst = 4;
+constexpr uint32_t kProbeNever = 0x9E3779B9u;
+struct ProbeSet {
+    const u32x4* src[kProbeMaxSrc];
+    u32x4* dst[kProbeMaxDst];
+};
+
+template <int R, int D>
+__global__ __launch_bounds__(kMaxBlock) void k_streams(ProbeSet ps, u32x4* __restrict__ sink, uint64_t n16, uint64_t block_base)
+{
+    const uint64_t i = (block_base + blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n16) return;
+    u32x4 acc = u32x4{uint32_t(i), 0u, 0u, 0u};
+    if constexpr (R > 0) {
+        u32x4 raw[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) raw[k] = load_once(ps.src[k] + i);
+        acc = raw[0];
+#pragma unroll
+        for (int k = 1; k < R; ++k) acc = acc ^ raw[k];
+    }
+    if constexpr (D > 0) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            u32x4 out = acc;
+            out[0] += uint32_t(d);
+            store_once(ps.dst[d] + i, out);
+        }
+    } else {
+        if (acc[0] == kProbeNever && acc[1] == kProbeNever && acc[2] == kProbeNever && acc[3] == kProbeNever) sink[0] = acc;
+    }
+}
+
 // ---- kernel: drain a snapshot to host memory at a bounded rate --------------------------
 // dst is pinned host memory mapped into the device's address space.  The grid is a handful of
 // blocks on purpose.  Measured on MI355X: while stores to the host saturate the link (this

@@ -615,6 +615,52 @@ def test_logical_launches_split_into_several(W, dtype, clip, refold):
         assert torch.equal(src, dst), limit
 
 
+@pytest.mark.parametrize("n_src,n_dst", [(0, 1), (0, 3), (1, 1), (2, 1), (4, 3), (7, 3), (8, 1), (16, 1), (4, 0), (16, 0)])
+def test_stream_probe_writes_what_it_says(n_src, n_dst):
+    """The bandwidth yardstick (a measurement aid, not part of the method): every destination holds the XOR of the
+    sources with the destination's index added to the first word; with no destination nothing is written."""
+    say("case stream probe", n_src, n_dst)
+    n = 1_000_003                                    # vectors: several blocks and a ragged last one
+    srcs = [torch.randint(-2 ** 31, 2 ** 31 - 1, (n, 4), dtype=torch.int32, device="cuda:0") for _ in range(n_src)]
+    dsts = [torch.full((n + 1, 4), 5, dtype=torch.int32, device="cuda:0") for _ in range(n_dst)]
+    sink = torch.full((4,), 5, dtype=torch.int32, device="cuda:0")
+    torch.cuda.synchronize()
+    for block, waves in ((0, 0), (64, 8), (1024, 32)):
+        rc = sh.shadow_stream_probe([d.data_ptr() for d in dsts], [x.data_ptr() for x in srcs], n * 16,
+                                    sink=sink.data_ptr() if n_dst == 0 else None, block=block, waves_per_cu=waves)
+        assert rc == binding.OK
+        torch.cuda.synchronize()
+        if n_src:
+            want = srcs[0].clone()
+            for x in srcs[1:]:
+                want ^= x
+        else:
+            want = torch.zeros((n, 4), dtype=torch.int32, device="cuda:0")
+            want[:, 0] = torch.arange(n, dtype=torch.int64, device="cuda:0").to(torch.int32)
+        for d, out in enumerate(dsts):
+            exp = want.clone()
+            exp[:, 0] += d                           # wraps like the kernel's unsigned add
+            assert torch.equal(out[:n], exp), (n_src, n_dst, d, block)
+            assert int(out[n].min()) == 5 and int(out[n].max()) == 5      # nothing past the end
+            out.fill_(5)
+        assert int(sink.min()) == 5 and int(sink.max()) == 5
+
+
+def test_stream_probe_in_place():
+    """Destinations that are sources as well, the shape of the optimizer sweep: every lane reads before it writes."""
+    say("case stream probe in place")
+    n = 300_007
+    srcs = [torch.randint(-2 ** 31, 2 ** 31 - 1, (n, 4), dtype=torch.int32, device="cuda:0") for _ in range(4)]
+    want = srcs[0] ^ srcs[1] ^ srcs[2] ^ srcs[3]
+    torch.cuda.synchronize()
+    assert sh.shadow_stream_probe([x.data_ptr() for x in srcs[1:]], [x.data_ptr() for x in srcs], n * 16, block=256, waves_per_cu=16) == binding.OK
+    torch.cuda.synchronize()
+    for d, out in enumerate(srcs[1:]):
+        exp = want.clone()
+        exp[:, 0] += d
+        assert torch.equal(out, exp), d
+
+
 def test_exactly_once_errors_leave_state_untouched():
     """Section 4.1: duplication or loss of a bucket must not go unnoticed."""
     say("case errors")

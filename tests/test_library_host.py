@@ -127,6 +127,14 @@ def test_null_handles_are_rejected():
     assert L.shadow_bucket_info(None, 0, None, None) == binding.EINVAL
     assert L.shadow_destroy(None) == binding.OK
     assert L.shadow_copy_probe(None, None, 16, None, 0) == binding.EINVAL
+    assert L.shadow_stream_probe(None, 1, None, 1, None, 16, None, 0, 0) == binding.EINVAL
+    assert sh.shadow_stream_probe([], [], 16) == binding.EINVAL                     # no stream at all
+    assert sh.shadow_stream_probe([256], [512], 24) == binding.EINVAL               # not a multiple of 16
+    assert sh.shadow_stream_probe([256], [512, 768, 1024], 16) == binding.EINVAL    # a mix the kernel is not built for
+    assert sh.shadow_stream_probe([256], [520], 16) == binding.EINVAL               # misaligned source
+    assert sh.shadow_stream_probe([], [512], 16) == binding.EINVAL                  # reads alone need the sink
+    assert sh.shadow_stream_probe([256], [512], 16, block=96) == binding.EINVAL
+    assert sh.shadow_stream_probe([256], [512], 0) == binding.OK                    # nothing to do
 
 
 def test_placement_advice():
