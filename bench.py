@@ -27,14 +27,14 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 # its defaults (profiles/*_bench_rocprofv3.md), each counter scaled by what it reads for the library's plain copy
 # kernel over 1 GiB.  Keyed by (workload, kernel, --refold, --no-clip); only reported for default settings and while
 # the kernel sources (comments and white space aside) still hash to the value the counters were taken at.
-MEASURED_TRAFFIC_SOURCES_SHA256 = "3ebe1dcc311c9e56557edc425889b8c08ab8a490a21a4c1f071a6fe3e776c7d2"
+MEASURED_TRAFFIC_SOURCES_SHA256 = "531afd3086483ae55f878199d9caaa6db5f9b3cd9f2c9cd291d7608a658f57b6"
 MEASURED_TRAFFIC = {
-    ("llama7b", "k_adamw", False, False): 188693086832.6,
-    ("ragged7b", "k_fold_sumsq", False, False): 5669608970.0,
-    ("gpt1p3b", "k_fold_sumsq", False, False): 4744641270.1,
-    ("llama7b_w1", "k_fold_adamw", True, False): 21902934861.0,
-    ("gpt2s", "k_fold_adamw", False, False): 4978203011.7,
-    ("llama7b", "k_fold_adamw", False, True): 11231865170.0,
+    ("llama7b", "k_adamw", False, False): 188710639377.5,
+    ("ragged7b", "k_fold_sumsq", False, False): 5669668469.5,
+    ("gpt1p3b", "k_fold_sumsq", False, False): 4744747317.0,
+    ("llama7b_w1", "k_fold_adamw", True, False): 21904072225.9,
+    ("gpt2s", "k_fold_adamw", False, False): 4978406394.8,
+    ("llama7b", "k_fold_adamw", False, True): 11232100632.0,
 }
 KERNEL_SOURCES = ("paper_2507_13522_amd/csrc/shadow_kernels.hip.h", "paper_2507_13522_amd/csrc/shadow.hip")
 
