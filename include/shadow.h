@@ -27,8 +27,9 @@
  *     issue them while a stream is being captured into a HIP graph.
  *   - Events and streams cross the boundary as void* holding a hipEvent_t /
  *     hipStream_t of the caller's HIP runtime.
- *   - Measurement aids (per-kernel timing, a copy kernel of known traffic) are
- *     declared in shadow_measure.h; they are not part of the method.
+ *   - Measurement aids (per-kernel timing, a copy kernel of known traffic, a
+ *     kernel that only streams a given mix of arrays) are declared in
+ *     shadow_measure.h; they are not part of the method.
  */
 #ifndef SHADOW_H
 #define SHADOW_H
