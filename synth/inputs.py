@@ -17,6 +17,7 @@ from .rng import grad_values, param_values, tiled
 from .workloads import Workload
 
 TILE_PERIOD = 1_000_003          # prime
+FILL_PIECE = 1 << 27             # elements filled per step on the device
 
 
 class Inputs:
@@ -83,18 +84,22 @@ class Inputs:
                 self._tiles_dev.pop(next(iter(self._tiles_dev)))
         return self._tiles_dev[key]
 
+    def _fill_tiled_dev(self, key, out: torch.Tensor, start: int) -> None:
+        """out[i] = tile[(start + i) mod period], in pieces so that the index arrays stay small beside a large out."""
+        tile, n = self._tile_dev(key), out.numel()
+        for s in range(0, n, FILL_PIECE):
+            k = min(FILL_PIECE, n - s)
+            idx = torch.arange(start + s, start + s + k, dtype=torch.int64, device=self.device)
+            torch.index_select(tile, 0, idx % self.period, out=out[s:s + k])
+
     def fill_grad_dev(self, out: torch.Tensor, step: int, w: int, start: int) -> None:
-        n = out.numel()
         if self.period:
-            idx = torch.arange(start, start + n, dtype=torch.int64, device=self.device)
-            torch.index_select(self._tile_dev((step, w)), 0, idx % self.period, out=out)
+            self._fill_tiled_dev((step, w), out, start)
         else:
-            out.copy_(self.grad_at(step, w, torch.arange(start, start + n, dtype=torch.int64)))
+            out.copy_(self.grad_at(step, w, torch.arange(start, start + out.numel(), dtype=torch.int64)))
 
     def fill_param_dev(self, out: torch.Tensor, start: int) -> None:
-        n = out.numel()
         if self.period:
-            idx = torch.arange(start, start + n, dtype=torch.int64, device=self.device)
-            torch.index_select(self._tile_dev("param"), 0, idx % self.period, out=out)
+            self._fill_tiled_dev("param", out, start)
         else:
-            out.copy_(self.param_at(torch.arange(start, start + n, dtype=torch.int64)))
+            out.copy_(self.param_at(torch.arange(start, start + out.numel(), dtype=torch.int64)))

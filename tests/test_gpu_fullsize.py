@@ -55,8 +55,9 @@ def pick_buckets(lay: oracle.Layout, budget: int):
 
 
 def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resident: bool, num_streams: int = 2,
-                 batch_bytes: int = 0, refold: bool = False, also_sizes=(), staged_last: bool = False):
-    wl = synth.get_workload(name)
+                 batch_bytes: int = 0, refold: bool = False, also_sizes=(), staged_last: bool = False, wl=None, also_elements=None):
+    """also_elements: {bucket: offsets inside it} joined to the scattered sample."""
+    wl = wl or synth.get_workload(name)
     say(f"case fullsize {name}: P={wl.num_params} W={wl.num_workers} steps={steps}")
     t_start = time.time()
     L = TILE_PERIOD
@@ -84,7 +85,10 @@ def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resi
         f"and {n_scatter} scattered elements")
     # scattered sample: logical indices, their arena positions and decay flags
     rng = np.random.default_rng(wl.seed % (2 ** 32))
-    sidx = np.unique(rng.integers(0, P, n_scatter))
+    sidx = rng.integers(0, P, n_scatter)
+    for b, offsets in (also_elements or {}).items():
+        sidx = np.concatenate([sidx, starts[b] + np.asarray(offsets, dtype=np.int64)])
+    sidx = np.unique(sidx)
     bstart = np.array(starts + [P])
     sb = np.searchsorted(bstart, sidx, side="right") - 1
     arena_off = np.array([off for off, _, _ in g.buckets])
@@ -208,3 +212,18 @@ def test_llama7b_single_reduced_gradient_full():
 
 def test_ragged7b_full():
     run_fullsize("ragged7b", steps=3, bucket_budget=30_000_000, n_scatter=5_000_000, resident=False, num_streams=4)
+
+
+@pytest.mark.parametrize("W,dtype,clip,refold", [(1, "bf16", 1.0, False), (1, "bf16", 1.0, True), (2, "f32", 0.0, False)])
+def test_bucket_beyond_two_to_the_32_elements(W, dtype, clip, refold):
+    """One tensor of 2^32 + 2^20 + 3 elements in a bucket of its own, between two small buckets: element indices, vector
+    indices times 16 and byte offsets inside one bucket all pass 2^32, and the bucket ends in a ragged tail.  The oracle
+    recomputes the small buckets and a scattered sample that includes the elements around 2^32 and the last ones."""
+    n = (1 << 32) + (1 << 20) + 3
+    ts = [synth.TensorSpec("head", 1000, True), synth.TensorSpec("giant", n, True), synth.TensorSpec("tail", 5000, False)]
+    wl = synth.Workload("giant", ts, num_workers=W, grad_dtype=dtype, grad_dist="normal", grad_sigma=1e-3, steps=2, max_grad_norm=clip,
+                        bucket_cap_bytes=1 << 20, weight_decay=0.01)
+    near = [0, 1, 2, 3, 4, (1 << 31) - 1, 1 << 31, (1 << 32) - 5, (1 << 32) - 1, 1 << 32, (1 << 32) + 1, (1 << 32) + 4, n - 8, n - 4, n - 3, n - 2, n - 1]
+    run_fullsize("giant", steps=2, bucket_budget=1_000_000, n_scatter=3_000_000, resident=True, num_streams=BENCH_STREAMS,
+                 batch_bytes=BENCH_BATCH_BYTES, refold=refold, wl=wl, also_elements={1: near})
+
