@@ -90,6 +90,7 @@ _SIGS = {
     "shadow_clip_state": [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_double)],
     "shadow_set_lr": [C.c_void_p, C.c_float],
     "shadow_profile_enable": [C.c_void_p, C.c_int32],
+    "shadow_profile_kinds": [C.c_void_p, C.c_uint32],
     "shadow_profile_read": [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_double)],
     "shadow_copy_probe": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64],
     "shadow_stream_probe": [C.POINTER(C.c_void_p), C.c_uint32, C.POINTER(C.c_void_p), C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p,
@@ -332,6 +333,9 @@ class Shadow:
 
     def profile_enable(self, on: bool) -> None:
         _check(lib().shadow_profile_enable(self._h, int(on)), "shadow_profile_enable")
+
+    def profile_kinds(self, kind_mask: int) -> None:
+        _check(lib().shadow_profile_kinds(self._h, kind_mask), "shadow_profile_kinds")
 
     def profile_read(self, kind: int) -> Tuple[int, float]:
         n, ms = C.c_uint64(), C.c_double()

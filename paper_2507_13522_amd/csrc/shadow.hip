@@ -160,6 +160,7 @@ struct shadow_ctx {
     std::vector<uint8_t> consumed_valid;
     // profiling
     bool profile = false;
+    uint32_t profile_kinds = ~0u;         // bit k: launches of kind k are bracketed while profiling is on
     struct Span { hipEvent_t a, b; };
     std::vector<Span> spans[SHADOW_K_COUNT];
     std::vector<hipEvent_t> ev_pool;
@@ -307,7 +308,7 @@ struct ProfScope {
     shadow_ctx* c; uint32_t kind; hipStream_t st; hipEvent_t a = nullptr, b = nullptr; int32_t rc = SHADOW_OK; bool on = true;
     ProfScope(shadow_ctx* c_, uint32_t k, hipStream_t s) : c(c_), kind(k), st(s)
     {
-        if (!c->profile || c->spans[k].size() >= kMaxSpansPerKind) { on = false; return; }
+        if (!c->profile || !((c->profile_kinds >> k) & 1u) || c->spans[k].size() >= kMaxSpansPerKind) { on = false; return; }
         rc = get_event(c, &a);
         if (rc == SHADOW_OK) rc = get_event(c, &b);
         if (rc == SHADOW_OK && hipEventRecord(a, st) != hipSuccess) rc = SHADOW_EHIP;
@@ -1515,6 +1516,13 @@ int32_t shadow_profile_enable(shadow_ctx* c, int32_t on)
 {
     if (!c) return SHADOW_EINVAL;
     c->profile = on != 0;
+    return SHADOW_OK;
+}
+
+int32_t shadow_profile_kinds(shadow_ctx* c, uint32_t kind_mask)
+{
+    if (!c || (kind_mask >> SHADOW_K_COUNT) != 0) return SHADOW_EINVAL;
+    c->profile_kinds = kind_mask;
     return SHADOW_OK;
 }
 

@@ -126,6 +126,7 @@ def test_null_handles_are_rejected():
     assert L.shadow_num_buckets(None, None) == binding.EINVAL
     assert L.shadow_bucket_info(None, 0, None, None) == binding.EINVAL
     assert L.shadow_destroy(None) == binding.OK
+    assert L.shadow_profile_kinds(None, 1) == binding.EINVAL
     assert L.shadow_copy_probe(None, None, 16, None, 0) == binding.EINVAL
     assert L.shadow_stream_probe(None, 1, None, 1, None, 16, None, 0, 0) == binding.EINVAL
     assert sh.shadow_stream_probe([], [], 16) == binding.EINVAL                     # no stream at all
