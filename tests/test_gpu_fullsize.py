@@ -183,13 +183,18 @@ def run_fullsize(name: str, steps: int, bucket_budget: int, n_scatter: int, resi
     del g, ring
 
 
-def test_gpt2_small_full():
-    run_fullsize("gpt2s", steps=20, bucket_budget=45_000_000, n_scatter=2_000_000, resident=True)
+@pytest.mark.parametrize("bench_config", [False, True])
+def test_gpt2_small_full(bench_config):
+    """Once with a launch per bucket on two streams, once as bench.py launches it (one stream, buckets batched)."""
+    kw = dict(num_streams=BENCH_STREAMS, batch_bytes=BENCH_BATCH_BYTES) if bench_config else {}
+    run_fullsize("gpt2s", steps=20, bucket_budget=45_000_000, n_scatter=2_000_000, resident=True, **kw)
 
 
 def test_gpt_1p3b_full():
-    """The last iteration is armed for a staged snapshot: its update kernels write a second set of arenas as well."""
-    run_fullsize("gpt1p3b", steps=10, bucket_budget=30_000_000, n_scatter=5_000_000, resident=True, staged_last=True)
+    """bench.py's launch configuration.  The last iteration is armed for a staged snapshot: its update kernels write a
+    second set of arenas as well."""
+    run_fullsize("gpt1p3b", steps=10, bucket_budget=30_000_000, n_scatter=5_000_000, resident=True, staged_last=True,
+                 num_streams=BENCH_STREAMS, batch_bytes=BENCH_BATCH_BYTES)
 
 
 def test_llama7b_full():
